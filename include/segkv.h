@@ -1,0 +1,131 @@
+/*
+ * libsegkv -- fused decode-step scaled-dot-product attention over a segment
+ * KV cache, for AMD MI355X (gfx950).  C ABI.
+ *
+ * Method: arxiv 2401.05391.  The KV cache of a batch of B requests decoded
+ * with beam width W is kept in two segments (Section 3.2):
+ *   prompt   K and V  [B, Lp, Hkv, D]        fp16, batch first, one copy per
+ *                                            request shared by its W beams;
+ *   response K and V  [Tcap, B*W, Hkv, D]    fp16, sequence first,
+ *                                            pre-allocated, rows 0..T-1 valid.
+ * One decode step of one layer (Section 3.1, decoding phase; Section 3.3)
+ * writes the step's K/V into response row T-1 and computes, for each of the
+ * B*W beam rows and Hq query heads, softmax attention of the single query
+ * token over the Lp prompt keys of its request and over the T response rows on
+ * its own beam lineage (the "index select" of Section 3.3, fused).
+ *
+ * Conventions common to all entry points
+ *   - Every tensor pointer is a DEVICE pointer to memory owned by the caller,
+ *     dense, row-major in the shape given, 16-byte aligned.  The library never
+ *     allocates, frees or retains caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls enqueue work on it and return without synchronising.
+ *   - `segkv_dims*` is a HOST pointer, read during the call only.
+ *   - Return value: SEGKV_OK (0), or a negative segkv_status; on error nothing
+ *     has been enqueued.  Faults raised later by the device (for example from
+ *     parent entries outside [0, beam)) are not reported by the call.
+ *   - Beam rows of request b are rows b*beam .. b*beam+beam-1.  Query head hq
+ *     reads KV head hq / (Hq/Hkv).
+ */
+#ifndef SEGKV_H
+#define SEGKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t B;     /* requests, >= 1                                            */
+    int32_t beam;  /* beam width W, 1..8                                        */
+    int32_t Hq;    /* query heads, multiple of Hkv                              */
+    int32_t Hkv;   /* key/value heads                                           */
+    int32_t D;     /* head dimension: 64, 128 or 256                            */
+    int32_t Lp;    /* prompt length, >= 0 (0: response segment only)            */
+    int32_t T;     /* valid response rows INCLUDING the current step, 1..Tcap   */
+    int32_t Tcap;  /* allocated rows of resp_k / resp_v                         */
+} segkv_dims;
+
+typedef enum {
+    SEGKV_OK = 0,
+    SEGKV_INVALID_ARG = -1,         /* null required pointer, bad dimension, t out of range,
+                                       only one of k_new / v_new given                        */
+    SEGKV_UNSUPPORTED = -2,         /* D or beam outside the compiled variants                */
+    SEGKV_MISALIGNED = -3,          /* a tensor base is not 16-byte aligned                   */
+    SEGKV_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes < segkv_workspace_bytes(d)             */
+    SEGKV_HIP_ERROR = -5            /* a launch was rejected by the HIP runtime               */
+} segkv_status;
+
+/*
+ * Append (Section 3.1: the step's Key_t / Value_t are kept in their row of the
+ * pre-allocated sequence-first response buffers, replacing the concatenation).
+ * Copies k_new, v_new [B*beam, Hkv, D] into row t of resp_k, resp_v
+ * [Tcap, B*beam, Hkv, D].  0 <= t < Tcap.  d->T, d->Lp and d->Hq are not used.
+ */
+int segkv_append_kv(void* resp_k, void* resp_v,
+                    const void* k_new, const void* v_new,
+                    int32_t t, const segkv_dims* d, void* stream);
+
+/*
+ * Fused decode-step attention (Section 3.3).
+ *   out           [B*beam, Hq, D] fp16, written.
+ *   q             [B*beam, Hq, D] fp16.
+ *   prompt_k/v    [B, Lp, Hkv, D] fp16 (may be NULL when Lp == 0).
+ *   resp_k/v      [Tcap, B*beam, Hkv, D] fp16.  Rows >= T are never read.
+ *   parent        [T, B*beam] int32 beam-search back pointers, request-local:
+ *                 parent[s][b*beam+j] in [0, beam) is the slot at step s-1 of the
+ *                 hypothesis that slot j extends at step s.  Row 0 (which points
+ *                 into the shared prompt) is ignored.  The library resolves the
+ *                 lineage itself: slot_at[T-1] = j, slot_at[s-1] =
+ *                 parent[s][b*beam + slot_at[s]].  May be NULL when beam == 1.
+ *                 Entries are not range-checked on the device.
+ *   k_new, v_new  both NULL, or both [B*beam, Hkv, D] fp16: the current step's
+ *                 K/V.  If given they are written to row T-1 of resp_k/resp_v
+ *                 by this call and used as that row; the previous content of
+ *                 row T-1 is never read.  Result and final buffer contents equal
+ *                 segkv_append_kv(..., t = T-1) followed by this call with NULLs.
+ *   alibi_slopes  NULL, or [Hq] fp32: slope[hq] * key_position is added to the
+ *                 scaled logit (prompt key i has position i, response step s has
+ *                 position Lp+s).  Not multiplied by `scale`.
+ *   anc_out       NULL, or [T, B*beam] int32, written with the resolved slot of
+ *                 every (step, beam row) exactly as the kernel used it.
+ *   workspace     device scratch of at least segkv_workspace_bytes(d) bytes,
+ *                 need not be initialised; contents undefined afterwards.
+ *   scale         logit scale, normally 1/sqrt(D).
+ * The single query token sits at position Lp+T-1 and attends to all Lp+T keys.
+ * Arithmetic: fp16 inputs, fp32 logits, softmax statistics and accumulation,
+ * output rounded to fp16 (round to nearest even).
+ * Concurrent calls must not share `workspace`, nor write the tensors read here.
+ */
+int segkv_sdpa_decode(void* out, const void* q,
+                      const void* prompt_k, const void* prompt_v,
+                      void* resp_k, void* resp_v,
+                      const int32_t* parent,
+                      const void* k_new, const void* v_new,
+                      const float* alibi_slopes,
+                      int32_t* anc_out,
+                      void* workspace, size_t workspace_bytes,
+                      float scale, const segkv_dims* d, void* stream);
+
+/* Bytes of device scratch segkv_sdpa_decode needs for these dimensions (the
+ * split-KV partial results of Section 3.3's accumulate step).  0 on invalid
+ * dimensions. */
+size_t segkv_workspace_bytes(const segkv_dims* d);
+
+/* Static, human-readable text for a status code. */
+const char* segkv_status_string(int status);
+
+/*
+ * Measurement helper: reads `bytes` bytes (multiple of 16) from `src` with
+ * 128-bit loads spread over the whole device and writes one checksum word per
+ * work-group to `sink` (>= 4096 * 4 bytes).  Gives the practical streaming-read
+ * ceiling of the device next to which attention timings are quoted.
+ */
+int segkv_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEGKV_H */

@@ -1,0 +1,116 @@
+"""Thin ctypes binding of libsegkv.so -- argument marshalling only.
+
+Every step of the decode attention runs inside the library's HIP kernels; this
+module just turns torch tensors into device pointers and sizes.  PyTorch is
+used for device memory and streams, nothing else.  There is no CPU fallback:
+if the library cannot be loaded the import of the entry points raises.
+
+Names and arguments mirror include/segkv.h.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional
+
+from . import build as _build
+
+SEGKV_OK = 0
+SEGKV_INVALID_ARG = -1
+SEGKV_UNSUPPORTED = -2
+SEGKV_MISALIGNED = -3
+SEGKV_WORKSPACE_TOO_SMALL = -4
+SEGKV_HIP_ERROR = -5
+
+EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
+           "segkv_status_string", "segkv_stream_read_probe")
+
+
+class SegkvDims(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "beam", "Hq", "Hkv", "D", "Lp", "T", "Tcap")]
+
+
+class SegkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load_library():
+    """Load libsegkv.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _build.is_built():
+        _build.build_library()
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    dp = ctypes.POINTER(SegkvDims)
+    lib.segkv_append_kv.restype = ctypes.c_int
+    lib.segkv_append_kv.argtypes = [vp, vp, vp, vp, i32, dp, vp]
+    lib.segkv_sdpa_decode.restype = ctypes.c_int
+    lib.segkv_sdpa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
+                                      ctypes.c_float, dp, vp]
+    lib.segkv_workspace_bytes.restype = sz
+    lib.segkv_workspace_bytes.argtypes = [dp]
+    lib.segkv_status_string.restype = ctypes.c_char_p
+    lib.segkv_status_string.argtypes = [ctypes.c_int]
+    lib.segkv_stream_read_probe.restype = ctypes.c_int
+    lib.segkv_stream_read_probe.argtypes = [vp, sz, vp, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().segkv_status_string(int(status)).decode()
+
+
+def make_dims(B, beam, Hq, Hkv, D, Lp, T, Tcap) -> SegkvDims:
+    return SegkvDims(B, beam, Hq, Hkv, D, Lp, T, Tcap)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("libsegkv takes contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def workspace_bytes(dims: SegkvDims) -> int:
+    return int(load_library().segkv_workspace_bytes(ctypes.byref(dims)))
+
+
+def append_kv(resp_k, resp_v, k_new, v_new, t: int, dims: SegkvDims, stream=None) -> None:
+    rc = load_library().segkv_append_kv(_ptr(resp_k), _ptr(resp_v), _ptr(k_new), _ptr(v_new),
+                                        int(t), ctypes.byref(dims), _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_append_kv")
+
+
+def sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvDims, scale: float,
+                k_new=None, v_new=None, alibi_slopes=None, anc_out=None, workspace=None,
+                stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load_library().segkv_sdpa_decode(
+        _ptr(out), _ptr(q), _ptr(prompt_k), _ptr(prompt_v), _ptr(resp_k), _ptr(resp_v),
+        _ptr(parent), _ptr(k_new), _ptr(v_new), _ptr(alibi_slopes), _ptr(anc_out),
+        _ptr(workspace), ws_bytes, float(scale), ctypes.byref(dims), _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_sdpa_decode")
+
+
+def stream_read_probe(src, sink, stream=None) -> None:
+    nbytes = (src.numel() * src.element_size()) // 16 * 16
+    rc = load_library().segkv_stream_read_probe(_ptr(src), nbytes, _ptr(sink),
+                                                _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_stream_read_probe")

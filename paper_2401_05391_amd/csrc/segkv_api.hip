@@ -1,0 +1,197 @@
+// libsegkv C-ABI layer: argument validation, launch planning, kernel launches.
+// Declarations and the full contract are in include/segkv.h.
+#include "segkv.h"
+
+#include <cstdlib>
+
+#include "segkv_launch.h"
+
+namespace {
+
+using segkv::SdpaParams;
+
+struct Plan {
+    int G, nq, QB, n_qblocks;
+    int merged, n_chunks, pchunk, rchunk, n_rchunks, n_pchunks;
+    size_t ws_ml_bytes, ws_acc_bytes;
+    unsigned grid;
+};
+
+int env_int(const char* name, int fallback)
+{
+    const char* s = std::getenv(name);
+    if (!s || !*s) return fallback;
+    const long v = std::strtol(s, nullptr, 10);
+    return v > 0 ? (int)v : fallback;
+}
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+bool dims_ok(const segkv_dims* d)
+{
+    return d && d->B >= 1 && d->beam >= 1 && d->Hkv >= 1 && d->Hq >= 1 && d->Hq % d->Hkv == 0 &&
+           d->D >= 1 && d->Lp >= 0 && d->T >= 1 && d->T <= d->Tcap;
+}
+
+bool dims_supported(const segkv_dims* d)
+{
+    return (d->D == 64 || d->D == 128 || d->D == 256) && d->beam <= 8;
+}
+
+// How the keys of one (request, KV head) unit are cut into work-groups.
+// Enough work-groups to occupy 256 CUs several times over, but chunks long
+// enough that the fp32 partials written per chunk stay small next to the K/V
+// bytes the chunk reads.
+Plan make_plan(const segkv_dims* d)
+{
+    Plan pl{};
+    pl.G = d->Hq / d->Hkv;
+    pl.nq = d->beam * pl.G;
+    pl.QB = (pl.nq == 1) ? 1 : 4;
+    pl.n_qblocks = ceil_div(pl.nq, pl.QB);
+    const long units = (long)d->B * d->Hkv * pl.n_qblocks;
+    const int target_groups = env_int("SEGKV_TARGET_GROUPS", 2048);
+    const int min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * pl.QB);
+
+    if (d->T <= segkv::kMaxStepsPerChunk && units >= target_groups) {
+        pl.merged = 1;
+        pl.n_chunks = 1;
+        pl.n_rchunks = 1;
+        pl.rchunk = d->T;
+        pl.n_pchunks = d->Lp > 0 ? 1 : 0;
+        pl.pchunk = d->Lp > 0 ? d->Lp : 1;
+    } else {
+        pl.merged = 0;
+        pl.n_rchunks = ceil_div(d->T, segkv::kMaxStepsPerChunk);
+        pl.rchunk = ceil_div(d->T, pl.n_rchunks);
+        if (d->Lp > 0) {
+            long want = (target_groups + units - 1) / units - pl.n_rchunks;
+            const int most = ceil_div(d->Lp, min_pchunk);
+            if (want < 1) want = 1;
+            if (want > most) want = most;
+            pl.pchunk = ceil_div(ceil_div(d->Lp, (int)want), 32) * 32;
+            pl.n_pchunks = ceil_div(d->Lp, pl.pchunk);
+        } else {
+            pl.pchunk = 1;
+            pl.n_pchunks = 0;
+        }
+        pl.n_chunks = pl.n_rchunks + pl.n_pchunks;
+    }
+    const size_t NQ = (size_t)d->B * d->beam * d->Hq;
+    if (pl.n_chunks > 1) {
+        pl.ws_ml_bytes = ((size_t)pl.n_chunks * NQ * 2 * sizeof(float) + 15) & ~(size_t)15;
+        pl.ws_acc_bytes = (size_t)pl.n_chunks * NQ * d->D * sizeof(float);
+    }
+    pl.grid = (unsigned)(units * pl.n_chunks);
+    return pl;
+}
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char* segkv_status_string(int status)
+{
+    switch (status) {
+        case SEGKV_OK: return "ok";
+        case SEGKV_INVALID_ARG: return "invalid argument";
+        case SEGKV_UNSUPPORTED: return "unsupported head dimension or beam width";
+        case SEGKV_MISALIGNED: return "tensor pointer is not 16-byte aligned";
+        case SEGKV_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case SEGKV_HIP_ERROR: return "HIP runtime rejected a kernel launch";
+        default: return "unknown status";
+    }
+}
+
+size_t segkv_workspace_bytes(const segkv_dims* d)
+{
+    if (!dims_ok(d) || !dims_supported(d)) return 0;
+    const Plan pl = make_plan(d);
+    return pl.ws_ml_bytes + pl.ws_acc_bytes;
+}
+
+int segkv_append_kv(void* resp_k, void* resp_v, const void* k_new, const void* v_new, int32_t t,
+                    const segkv_dims* d, void* stream)
+{
+    if (!d || !resp_k || !resp_v || !k_new || !v_new) return SEGKV_INVALID_ARG;
+    if (d->B < 1 || d->beam < 1 || d->Hkv < 1 || d->D < 1 || d->Tcap < 1) return SEGKV_INVALID_ARG;
+    if (t < 0 || t >= d->Tcap) return SEGKV_INVALID_ARG;
+    if ((d->D % 8) != 0) return SEGKV_UNSUPPORTED;
+    if (misaligned(resp_k) || misaligned(resp_v) || misaligned(k_new) || misaligned(v_new))
+        return SEGKV_MISALIGNED;
+    const size_t row_bytes = (size_t)d->B * d->beam * d->Hkv * d->D * 2;
+    char* dk = (char*)resp_k + (size_t)t * row_bytes;
+    char* dv = (char*)resp_v + (size_t)t * row_bytes;
+    const hipError_t e = segkv::launch_append_kv(dk, dv, k_new, v_new, row_bytes, (hipStream_t)stream);
+    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+}
+
+int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void* prompt_v,
+                      void* resp_k, void* resp_v, const int32_t* parent, const void* k_new,
+                      const void* v_new, const float* alibi_slopes, int32_t* anc_out,
+                      void* workspace, size_t workspace_bytes, float scale, const segkv_dims* d,
+                      void* stream)
+{
+    if (!dims_ok(d)) return SEGKV_INVALID_ARG;
+    if (!out || !q || !resp_k || !resp_v) return SEGKV_INVALID_ARG;
+    if (d->Lp > 0 && (!prompt_k || !prompt_v)) return SEGKV_INVALID_ARG;
+    if (d->beam > 1 && !parent) return SEGKV_INVALID_ARG;
+    if ((k_new == nullptr) != (v_new == nullptr)) return SEGKV_INVALID_ARG;
+    if (!dims_supported(d)) return SEGKV_UNSUPPORTED;
+    if ((long)d->B * d->beam * d->Hq > (1L << 28)) return SEGKV_UNSUPPORTED;
+    if (misaligned(out) || misaligned(q) || misaligned(resp_k) || misaligned(resp_v) ||
+        (d->Lp > 0 && (misaligned(prompt_k) || misaligned(prompt_v))) ||
+        (k_new && (misaligned(k_new) || misaligned(v_new))) || misaligned(workspace) ||
+        ((uintptr_t)parent & 3u) || ((uintptr_t)alibi_slopes & 3u) || ((uintptr_t)anc_out & 3u))
+        return SEGKV_MISALIGNED;
+
+    const Plan pl = make_plan(d);
+    const size_t need = pl.ws_ml_bytes + pl.ws_acc_bytes;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return SEGKV_WORKSPACE_TOO_SMALL;
+
+    SdpaParams p{};
+    p.q = (const _Float16*)q;
+    p.out = (_Float16*)out;
+    p.prompt_k = (const _Float16*)prompt_k;
+    p.prompt_v = (const _Float16*)prompt_v;
+    p.resp_k = (_Float16*)resp_k;
+    p.resp_v = (_Float16*)resp_v;
+    p.parent = parent;
+    p.k_new = (const _Float16*)k_new;
+    p.v_new = (const _Float16*)v_new;
+    p.slopes = alibi_slopes;
+    p.anc_out = anc_out;
+    p.ws_ml = need ? (float*)workspace : nullptr;
+    p.ws_acc = need ? (float*)((char*)workspace + pl.ws_ml_bytes) : nullptr;
+    p.scale2 = scale * 1.4426950408889634f;
+    p.B = d->B; p.W = d->beam; p.Hq = d->Hq; p.Hkv = d->Hkv; p.G = pl.G; p.Lp = d->Lp; p.T = d->T;
+    p.nq = pl.nq;
+    p.n_qblocks = pl.n_qblocks;
+    p.merged = pl.merged;
+    p.n_chunks = pl.n_chunks;
+    p.pchunk = pl.pchunk;
+    p.rchunk = pl.rchunk;
+    p.n_rchunks = pl.n_rchunks;
+
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.grid, st);
+    if (e != hipSuccess) return SEGKV_HIP_ERROR;
+    if (pl.n_chunks > 1) {
+        e = segkv::launch_sdpa_merge(p.out, p.ws_ml, p.ws_acc, d->B * d->beam * d->Hq, d->D,
+                                     pl.n_chunks, st);
+        if (e != hipSuccess) return SEGKV_HIP_ERROR;
+    }
+    return SEGKV_OK;
+}
+
+int segkv_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream)
+{
+    if (!src || !sink || bytes == 0 || (bytes & 15u)) return SEGKV_INVALID_ARG;
+    if (misaligned(src) || ((uintptr_t)sink & 3u)) return SEGKV_MISALIGNED;
+    const hipError_t e = segkv::launch_stream_read_probe(src, bytes, sink, (hipStream_t)stream);
+    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+}
+
+}  // extern "C"

@@ -1,0 +1,597 @@
+// libsegkv device code: fused decode-step attention over a segment KV cache
+// (arxiv 2401.05391, Section 3.3) for gfx950, vector-ALU path.
+//
+// Work decomposition
+//   unit   = (request b, KV head g): the W*G queries (W beams x G grouped query
+//            heads) that share every prompt K/V row of that head.
+//   qblock = QB of those queries handled together by one work-group.
+//   chunk  = a slice of the unit's keys: either a range of prompt positions or
+//            a range of response steps.  With one chunk the work-group writes
+//            the fp16 context itself; with more it writes an (m, l, acc)
+//            partial per query and sdpa_merge_kernel combines them.
+//   Inside a work-group the 4 waves take key tiles round-robin.  A wave reads
+//   R = 64/LPR rows per 128-bit load (LPR lanes of 16 bytes cover one row
+//   slice), keeps one online-softmax state per lane group, and the states are
+//   merged across lane groups (shuffles) and waves (LDS) at the end.
+//
+// Response rows are visited through a compacted list of the distinct
+// (step, slot) rows that some beam of the request descends from, each with the
+// mask of beams that see it, so a row shared by several beams is read once.
+#include "segkv_common.h"
+#include "segkv_launch.h"
+
+namespace segkv {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+static_assert(kMaxStepsPerChunk == kThreads, "one thread per response step of a chunk");
+
+__device__ __forceinline__ uint4 load16(const _Float16* p)
+{
+    return *reinterpret_cast<const uint4*>(p);
+}
+__device__ __forceinline__ void store16(_Float16* p, uint4 v)
+{
+    *reinterpret_cast<uint4*>(p) = v;
+}
+__device__ __forceinline__ half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
+
+// ---------------------------------------------------------------------------
+// Ancestor resolution for the response steps [s0, s1) of request b
+// (Section 3.3, index select).  With P_s the packed parent map of step s, the
+// slot map of step s is A_s = P_{s+1} o P_{s+2} o ... o P_{T-1} (A_{T-1} = id),
+// i.e. a suffix composition: computed as an ordered tree reduction for the
+// steps after the chunk and a block-wide suffix scan inside it.
+// Leaves in LDS: ent[0..total) = (local step << 16) | (slot << 8) | beam mask
+// for every distinct row referenced, ordered by step.  All threads must call.
+// ---------------------------------------------------------------------------
+struct ResponseListSmem {
+    uint32_t map[2][kThreads];
+    int cnt[2][kThreads];
+    uint32_t ent[kThreads * 8];
+    int total;
+};
+
+__device__ __forceinline__ uint32_t load_parent_map(const int32_t* parent, int N, int W, int b, int s)
+{
+    const int32_t* row = parent + (size_t)s * N + (size_t)b * W;
+    uint32_t f = kIdentityMap;
+    for (int x = 0; x < W; ++x) {
+        // entries are trusted to lie in [0, W); clamping keeps a bad table inside
+        // the request's own rows instead of reading past the buffers
+        const uint32_t v = (uint32_t)min(max(row[x], 0), W - 1);
+        f = (f & ~(15u << (4 * x))) | (v << (4 * x));
+    }
+    return f;
+}
+
+__device__ void build_response_list(ResponseListSmem& sm, const int32_t* parent, int32_t* anc_out,
+                                    int B, int W, int T, int b, int s0, int s1)
+{
+    const int t = threadIdx.x;
+    const int n = s1 - s0;
+    const int N = B * W;
+    if (W == 1) {
+        if (t < n) {
+            sm.ent[t] = ((uint32_t)t << 16) | 1u;
+            if (anc_out) anc_out[(size_t)(s0 + t) * N + b] = 0;
+        }
+        if (t == 0) sm.total = n;
+        __syncthreads();
+        return;
+    }
+
+    // (1) carry = A_{s1-1} = P_{s1} o ... o P_{T-1}
+    uint32_t carry = kIdentityMap;
+    const int later = T - s1;
+    if (later > 0) {
+        const int per = (later + kThreads - 1) / kThreads;
+        const int lo = s1 + t * per;
+        const int hi = min(lo + per, T);
+        uint32_t c = kIdentityMap;
+        for (int s = lo; s < hi; ++s) c = map_compose(c, load_parent_map(parent, N, W, b, s));
+        sm.map[0][t] = c;
+        for (int stride = 1; stride < kThreads; stride <<= 1) {
+            __syncthreads();
+            if ((t & (2 * stride - 1)) == 0)
+                sm.map[0][t] = map_compose(sm.map[0][t], sm.map[0][t + stride]);
+        }
+        __syncthreads();
+        carry = sm.map[0][0];
+        __syncthreads();
+    }
+
+    // (2) inclusive suffix scan of y_t = P_{s0+t+1} (t < n-1), y_{n-1} = carry
+    uint32_t y = kIdentityMap;
+    if (t < n - 1) y = load_parent_map(parent, N, W, b, s0 + t + 1);
+    else if (t == n - 1) y = carry;
+    int cur = 0;
+    sm.map[0][t] = y;
+    __syncthreads();
+    for (int off = 1; off < kThreads; off <<= 1) {
+        uint32_t x = sm.map[cur][t];
+        if (t + off < kThreads) x = map_compose(x, sm.map[cur][t + off]);
+        sm.map[cur ^ 1][t] = x;
+        cur ^= 1;
+        __syncthreads();
+    }
+    const uint32_t A = sm.map[cur][t];   // slot map of step s0+t
+
+    // (3) distinct slots referenced at this step
+    uint32_t present = 0;
+    if (t < n)
+        for (int j = 0; j < W; ++j) present |= 1u << map_get(A, j);
+    const int mine = __popc(present);
+    int ccur = 0;
+    sm.cnt[0][t] = mine;
+    __syncthreads();
+    for (int off = 1; off < kThreads; off <<= 1) {
+        int x = sm.cnt[ccur][t];
+        if (t >= off) x += sm.cnt[ccur][t - off];
+        sm.cnt[ccur ^ 1][t] = x;
+        ccur ^= 1;
+        __syncthreads();
+    }
+    int pos = sm.cnt[ccur][t] - mine;    // exclusive prefix
+    if (t == kThreads - 1) sm.total = sm.cnt[ccur][t];
+
+    // (4) entries, and the resolved table if asked for
+    if (t < n) {
+        for (int u = 0; u < W; ++u) {
+            if (present & (1u << u)) {
+                uint32_t mask = 0;
+                for (int j = 0; j < W; ++j)
+                    if (map_get(A, j) == (uint32_t)u) mask |= 1u << j;
+                sm.ent[pos++] = ((uint32_t)t << 16) | ((uint32_t)u << 8) | mask;
+            }
+        }
+        if (anc_out)
+            for (int j = 0; j < W; ++j)
+                anc_out[(size_t)(s0 + t) * N + (size_t)b * W + j] = (int32_t)map_get(A, j);
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// Main kernel
+// ---------------------------------------------------------------------------
+template <int D>
+struct Geometry {
+    static constexpr int LPR = (D >= 128) ? 16 : D / 8;   // lanes per key row
+    static constexpr int NV = D / (8 * LPR);              // 16-byte vectors per lane per row
+    static constexpr int R = 64 / LPR;                    // rows per wave-wide load
+    static constexpr int U = (NV == 1) ? 4 : 2;           // loads in flight per operand
+    static constexpr int EPL = NV * 8;                    // head-dim elements per lane
+};
+
+template <int D, int QB>
+struct MergeSmem {
+    float ml[kWaves][QB][2];
+    float acc[kWaves][QB][D];
+};
+
+template <int D, int QB>
+__global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
+{
+    using Geo = Geometry<D>;
+    constexpr int LPR = Geo::LPR, NV = Geo::NV, R = Geo::R, U = Geo::U, EPL = Geo::EPL;
+    constexpr int TILE = R * U;
+
+    __shared__ ResponseListSmem s_list;
+    __shared__ MergeSmem<D, QB> s_merge;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int c = lane % LPR;     // 16-byte column of the row slice
+    const int r = lane / LPR;     // row within a wave-wide load
+
+    // ---- which work item ----
+    int id = blockIdx.x;
+    const int qb = id % p.n_qblocks; id /= p.n_qblocks;
+    const int g = id % p.Hkv;        id /= p.Hkv;
+    const int chunk = id % p.n_chunks;
+    const int b = id / p.n_chunks;
+    const int N = p.B * p.W;
+
+    // merged: one work-group walks the whole prompt and the whole response;
+    // otherwise a chunk is a slice of response steps or of prompt positions.
+    int k0 = 0, k1 = 0, s0 = 0, s1 = 0;
+    if (p.merged) {
+        k1 = p.Lp;
+        s1 = p.T;
+    } else if (chunk < p.n_rchunks) {
+        s0 = chunk * p.rchunk;
+        s1 = min(s0 + p.rchunk, p.T);
+    } else {
+        k0 = (chunk - p.n_rchunks) * p.pchunk;
+        k1 = min(k0 + p.pchunk, p.Lp);
+    }
+    const bool direct_out = (p.n_chunks == 1);
+
+    // ---- queries of this block ----
+    half2_t qv[QB][NV * 4];
+    float slope2[QB];
+    int qbeam[QB];
+#pragma unroll
+    for (int qi = 0; qi < QB; ++qi) {
+        // queries past the end of the unit repeat the last one and are not stored
+        const int lq = min(qb * QB + qi, p.nq - 1);
+        const int j = lq / p.G;
+        const int hq = g * p.G + (lq % p.G);
+        qbeam[qi] = j;
+        const size_t qoff = ((size_t)(b * p.W + j) * p.Hq + hq) * D;
+        slope2[qi] = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const uint4 w = load16(p.q + qoff + v * (LPR * 8) + c * 8);
+            qv[qi][v * 4 + 0] = as_half2(w.x);
+            qv[qi][v * 4 + 1] = as_half2(w.y);
+            qv[qi][v * 4 + 2] = as_half2(w.z);
+            qv[qi][v * 4 + 3] = as_half2(w.w);
+        }
+    }
+    const int qpos = p.Lp + p.T - 1;
+
+    // ---- fused append: the block that owns step T-1 copies the unit's new rows ----
+    const bool have_new = (p.k_new != nullptr);
+    if (have_new && qb == 0 && s1 == p.T && s0 < s1) {
+        const int vec_per_row = D / 8;
+        const int total = p.W * vec_per_row * 2;
+        for (int i = tid; i < total; i += kThreads) {
+            const int which = i / (p.W * vec_per_row);
+            const int rem = i % (p.W * vec_per_row);
+            const int u = rem / vec_per_row;
+            const int col = rem % vec_per_row;
+            const size_t src = ((size_t)(b * p.W + u) * p.Hkv + g) * D + col * 8;
+            const size_t dst = (((size_t)(p.T - 1) * N + b * p.W + u) * p.Hkv + g) * D + col * 8;
+            if (which == 0) store16(p.resp_k + dst, load16(p.k_new + src));
+            else            store16(p.resp_v + dst, load16(p.v_new + src));
+        }
+    }
+
+    // ---- online softmax state, one per lane group ----
+    float m[QB], l[QB], acc[QB][EPL];
+#pragma unroll
+    for (int qi = 0; qi < QB; ++qi) {
+        m[qi] = kEmptyMax;
+        l[qi] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[qi][e] = 0.0f;
+    }
+
+    struct Tile {
+        uint4 k[U][NV];
+        uint4 v[U][NV];
+        int kpos[U];
+        uint32_t bmask[U];   // beams that see the row; 0 = row not valid
+    };
+
+    auto consume = [&](const Tile& t) {
+#pragma unroll
+        for (int qi = 0; qi < QB; ++qi) {
+            float z[U];
+            float m_new = m[qi];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float d = 0.0f;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    d = __builtin_amdgcn_fdot2(qv[qi][v * 4 + 0], as_half2(t.k[u][v].x), d, false);
+                    d = __builtin_amdgcn_fdot2(qv[qi][v * 4 + 1], as_half2(t.k[u][v].y), d, false);
+                    d = __builtin_amdgcn_fdot2(qv[qi][v * 4 + 2], as_half2(t.k[u][v].z), d, false);
+                    d = __builtin_amdgcn_fdot2(qv[qi][v * 4 + 3], as_half2(t.k[u][v].w), d, false);
+                }
+                d = group_allreduce_sum<LPR>(d);
+                const float zz = d * p.scale2 + slope2[qi] * (float)(t.kpos[u] - qpos);
+                const bool vis = (t.bmask[u] >> qbeam[qi]) & 1u;
+                z[u] = vis ? zz : -INFINITY;
+                m_new = fmaxf(m_new, z[u]);
+            }
+            const float corr = fast_exp2(m[qi] - m_new);
+            m[qi] = m_new;
+            float pu[U];
+            float psum = 0.0f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                pu[u] = fast_exp2(z[u] - m_new);
+                psum += pu[u];
+            }
+            l[qi] = l[qi] * corr + psum;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[qi][e] *= corr;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const uint32_t w[4] = {t.v[u][v].x, t.v[u][v].y, t.v[u][v].z, t.v[u][v].w};
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        const half2_t hv = as_half2(w[h]);
+                        acc[qi][v * 8 + 2 * h + 0] = fmaf(pu[u], (float)hv.x, acc[qi][v * 8 + 2 * h + 0]);
+                        acc[qi][v * 8 + 2 * h + 1] = fmaf(pu[u], (float)hv.y, acc[qi][v * 8 + 2 * h + 1]);
+                    }
+                }
+            }
+        }
+    };
+
+    // ---- prompt segment (Section 3.3: loop over the prompt keys, FlashAttention style) ----
+    if (k1 > k0) {
+        const int n_tiles = (k1 - k0 + TILE - 1) / TILE;
+        auto fetch = [&](Tile& t, int ti) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = k0 + ti * TILE + u * R + r;
+                const bool ok = i < k1;
+                const int ic = ok ? i : (k1 - 1);
+                const size_t off = (((size_t)b * p.Lp + ic) * p.Hkv + g) * D + c * 8;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    t.k[u][v] = load16(p.prompt_k + off + v * (LPR * 8));
+                    t.v[u][v] = load16(p.prompt_v + off + v * (LPR * 8));
+                }
+                t.kpos[u] = ic;
+                t.bmask[u] = ok ? 0xffu : 0u;
+            }
+        };
+        Tile cur, nxt;
+        int ti = wave;
+        if (ti < n_tiles) fetch(cur, ti);
+        for (; ti < n_tiles; ti += kWaves) {
+            const bool more = (ti + kWaves) < n_tiles;
+            if (more) fetch(nxt, ti + kWaves);
+            consume(cur);
+            if (more) cur = nxt;
+        }
+    }
+
+    // ---- response segment (index select fused: rows chosen by the beam lineage) ----
+    if (s1 > s0) {
+        build_response_list(s_list, p.parent,
+                            (g == 0 && qb == 0) ? p.anc_out : nullptr,
+                            p.B, p.W, p.T, b, s0, s1);
+        const int total = s_list.total;
+        const int n_tiles = (total + TILE - 1) / TILE;
+        auto fetch = [&](Tile& t, int ti) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int e = ti * TILE + u * R + r;
+                const bool ok = e < total;
+                const uint32_t ent = s_list.ent[ok ? e : (total - 1)];
+                const int s = s0 + (int)(ent >> 16);
+                const int slot = (int)((ent >> 8) & 0xffu);
+                const _Float16* kp;
+                const _Float16* vp;
+                if (have_new && s == p.T - 1) {
+                    const size_t off = ((size_t)(b * p.W + slot) * p.Hkv + g) * D + c * 8;
+                    kp = p.k_new + off;
+                    vp = p.v_new + off;
+                } else {
+                    const size_t off = (((size_t)s * N + b * p.W + slot) * p.Hkv + g) * D + c * 8;
+                    kp = p.resp_k + off;
+                    vp = p.resp_v + off;
+                }
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    t.k[u][v] = load16(kp + v * (LPR * 8));
+                    t.v[u][v] = load16(vp + v * (LPR * 8));
+                }
+                t.kpos[u] = p.Lp + s;
+                t.bmask[u] = ok ? (ent & 0xffu) : 0u;
+            }
+        };
+        Tile cur, nxt;
+        int ti = wave;
+        if (ti < n_tiles) fetch(cur, ti);
+        for (; ti < n_tiles; ti += kWaves) {
+            const bool more = (ti + kWaves) < n_tiles;
+            if (more) fetch(nxt, ti + kWaves);
+            consume(cur);
+            if (more) cur = nxt;
+        }
+    }
+
+    // ---- merge lane groups of the wave (butterfly over the row index) ----
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+        for (int qi = 0; qi < QB; ++qi) {
+            const float mo = __shfl_xor(m[qi], off);
+            const float lo = __shfl_xor(l[qi], off);
+            const float mn = fmaxf(m[qi], mo);
+            const float a = fast_exp2(m[qi] - mn);
+            const float bb = fast_exp2(mo - mn);
+            l[qi] = l[qi] * a + lo * bb;
+            m[qi] = mn;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                const float ao = __shfl_xor(acc[qi][e], off);
+                acc[qi][e] = acc[qi][e] * a + ao * bb;
+            }
+        }
+    }
+
+    // ---- merge the waves through LDS ----
+    if (r == 0) {
+#pragma unroll
+        for (int qi = 0; qi < QB; ++qi) {
+            if (c == 0) {
+                s_merge.ml[wave][qi][0] = m[qi];
+                s_merge.ml[wave][qi][1] = l[qi];
+            }
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    s_merge.acc[wave][qi][v * (LPR * 8) + c * 8 + e] = acc[qi][v * 8 + e];
+        }
+    }
+    __syncthreads();
+
+    const int NQ = N * p.Hq;
+    for (int idx = tid; idx < QB * D; idx += kThreads) {
+        const int qi = idx / D;
+        const int d = idx % D;
+        if (qb * QB + qi >= p.nq) continue;
+        float mm = s_merge.ml[0][qi][0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, s_merge.ml[w][qi][0]);
+        float ll = 0.0f, aa = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float f = fast_exp2(s_merge.ml[w][qi][0] - mm);
+            ll += s_merge.ml[w][qi][1] * f;
+            aa += s_merge.acc[w][qi][d] * f;
+        }
+        const int lq = qb * QB + qi;
+        const int j = lq / p.G;
+        const int hq = g * p.G + (lq % p.G);
+        const size_t qidx = (size_t)(b * p.W + j) * p.Hq + hq;
+        if (direct_out) {
+            p.out[qidx * D + d] = (_Float16)(aa / ll);
+        } else {
+            p.ws_acc[((size_t)chunk * NQ + qidx) * D + d] = aa;
+            if (d == 0) {
+                p.ws_ml[((size_t)chunk * NQ + qidx) * 2 + 0] = mm;
+                p.ws_ml[((size_t)chunk * NQ + qidx) * 2 + 1] = ll;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Merge pass over chunks (Section 3.3: the partial contexts are accumulated
+// together): out = sum_c acc_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
+// One thread per (query row, 4 consecutive head-dim elements).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void sdpa_merge_kernel(_Float16* out, const float* ws_ml,
+                                                         const float* ws_acc, int NQ, int D,
+                                                         int n_chunks)
+{
+    const int per_row = D / 4;
+    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= (size_t)NQ * per_row) return;
+    const size_t qidx = gid / per_row;
+    const int d4 = (int)(gid % per_row) * 4;
+    float mm = kEmptyMax;
+    for (int ch = 0; ch < n_chunks; ++ch)
+        mm = fmaxf(mm, ws_ml[((size_t)ch * NQ + qidx) * 2]);
+    float ll = 0.0f;
+    float4_t aa = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const float2 ml = *reinterpret_cast<const float2*>(ws_ml + ((size_t)ch * NQ + qidx) * 2);
+        const float f = fast_exp2(ml.x - mm);
+        ll += ml.y * f;
+        const float4_t a =
+            *reinterpret_cast<const float4_t*>(ws_acc + ((size_t)ch * NQ + qidx) * D + d4);
+        aa += a * f;
+    }
+    const float inv = 1.0f / ll;
+    half4_t o;
+    o.x = (_Float16)(aa.x * inv);
+    o.y = (_Float16)(aa.y * inv);
+    o.z = (_Float16)(aa.z * inv);
+    o.w = (_Float16)(aa.w * inv);
+    *reinterpret_cast<half4_t*>(out + qidx * D + d4) = o;
+}
+
+// ---------------------------------------------------------------------------
+// Append (Section 3.1): row t of the response buffers := the step's K/V.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void append_kv_kernel(uint4* __restrict__ dst_k,
+                                                        uint4* __restrict__ dst_v,
+                                                        const uint4* __restrict__ src_k,
+                                                        const uint4* __restrict__ src_v,
+                                                        size_t n_vec)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
+        dst_k[i] = src_k[i];
+        dst_v[i] = src_v[i];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Streaming-read probe: the practical HBM read ceiling for this access shape.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void stream_read_probe_kernel(const uint4* __restrict__ src,
+                                                                size_t n_vec, uint32_t* sink)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint32_t x = 0;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        const uint4 a = src[i];
+        const uint4 b = src[i + stride];
+        const uint4 c = src[i + 2 * stride];
+        const uint4 d = src[i + 3 * stride];
+        x ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w;
+        x ^= c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n_vec; i += stride) {
+        const uint4 a = src[i];
+        x ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    // one word per work-group; the xor keeps every load live
+    __shared__ uint32_t red[256];
+    red[threadIdx.x] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t y = 0;
+        for (int k = 0; k < 256; ++k) y ^= red[k];
+        sink[blockIdx.x] = y;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host-side launchers
+// ---------------------------------------------------------------------------
+template <int D>
+static hipError_t launch_sdpa_d(const SdpaParams& p, int QB, unsigned grid, hipStream_t st)
+{
+    if (QB == 1) hipLaunchKernelGGL((sdpa_decode_alu_kernel<D, 1>), dim3(grid), dim3(kThreads), 0, st, p);
+    else         hipLaunchKernelGGL((sdpa_decode_alu_kernel<D, 4>), dim3(grid), dim3(kThreads), 0, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, unsigned grid, hipStream_t st)
+{
+    switch (D) {
+        case 64:  return launch_sdpa_d<64>(p, QB, grid, st);
+        case 128: return launch_sdpa_d<128>(p, QB, grid, st);
+        case 256: return launch_sdpa_d<256>(p, QB, grid, st);
+        default:  return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_acc, int NQ, int D,
+                             int n_chunks, hipStream_t st)
+{
+    const size_t threads = (size_t)NQ * (D / 4);
+    const unsigned grid = (unsigned)((threads + 255) / 256);
+    hipLaunchKernelGGL(sdpa_merge_kernel, dim3(grid), dim3(256), 0, st, out, ws_ml, ws_acc, NQ, D,
+                       n_chunks);
+    return hipGetLastError();
+}
+
+hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const void* src_v,
+                            size_t bytes, hipStream_t st)
+{
+    const size_t n_vec = bytes / 16;
+    unsigned grid = (unsigned)((n_vec + 255) / 256);
+    if (grid > 2048u) grid = 2048u;
+    if (grid == 0) grid = 1;
+    hipLaunchKernelGGL(append_kv_kernel, dim3(grid), dim3(256), 0, st, (uint4*)dst_k, (uint4*)dst_v,
+                       (const uint4*)src_k, (const uint4*)src_v, n_vec);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st)
+{
+    hipLaunchKernelGGL(stream_read_probe_kernel, dim3(kProbeGroups), dim3(256), 0, st,
+                       (const uint4*)src, bytes / 16, (uint32_t*)sink);
+    return hipGetLastError();
+}
+
+}  // namespace segkv

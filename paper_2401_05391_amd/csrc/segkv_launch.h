@@ -1,0 +1,46 @@
+// Internal interface between the C-ABI layer (segkv_api.hip) and the device
+// code (segkv_kernels.hip).  Not installed; not part of the public boundary.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace segkv {
+
+struct SdpaParams {
+    const _Float16* q;
+    _Float16* out;
+    const _Float16* prompt_k;
+    const _Float16* prompt_v;
+    _Float16* resp_k;
+    _Float16* resp_v;
+    const int32_t* parent;
+    const _Float16* k_new;
+    const _Float16* v_new;
+    const float* slopes;
+    int32_t* anc_out;
+    float* ws_ml;    // [n_chunks][NQ][2]
+    float* ws_acc;   // [n_chunks][NQ][D]
+    float scale2;    // scale * log2(e)
+    int B, W, Hq, Hkv, G, Lp, T;
+    int nq;          // W * G queries per unit
+    int n_qblocks;
+    int merged;      // 1: a single work-group per (unit, qblock) covers prompt and response
+    int n_chunks;    // partials per query (1 => the main kernel writes `out` itself)
+    int pchunk;      // prompt positions per chunk
+    int rchunk;      // response steps per chunk (<= kMaxStepsPerChunk)
+    int n_rchunks;   // response chunks come first in the chunk index
+};
+
+
+constexpr int kMaxStepsPerChunk = 256;   // response steps one work-group can resolve
+constexpr int kProbeGroups = 4096;       // work-groups (and sink words) of the read probe
+
+hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, unsigned grid, hipStream_t st);
+hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_acc, int NQ, int D,
+                             int n_chunks, hipStream_t st);
+hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const void* src_v,
+                            size_t bytes, hipStream_t st);
+hipError_t launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
+
+}  // namespace segkv

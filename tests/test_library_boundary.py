@@ -1,0 +1,97 @@
+"""CPU-side checks of the C-ABI boundary: the library loads, exports every
+declared symbol, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2401_05391_amd as segkv
+from paper_2401_05391_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "segkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(segkv_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = segkv.load_library()
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_dims_struct_matches_header():
+    text = open(os.path.join(ROOT, "include", "segkv.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} segkv_dims;", text, flags=re.S).group(1)
+    fields = re.findall(r"int32_t\s+(\w+);", body)
+    assert fields == [f[0] for f in binding.SegkvDims._fields_]
+    assert ctypes.sizeof(binding.SegkvDims) == 4 * len(fields)
+
+
+def test_status_strings():
+    assert segkv.status_string(0) == "ok"
+    seen = {segkv.status_string(c) for c in range(-5, 1)}
+    assert len(seen) == 6
+    assert segkv.status_string(-99) == "unknown status"
+
+
+FAKE = 0x7f0000001000  # non-null, 16-byte aligned; never dereferenced: every call below is rejected
+
+
+def _decode(dims, **kw):
+    lib = segkv.load_library()
+    a = dict(out=FAKE, q=FAKE, pk=FAKE, pv=FAKE, rk=FAKE, rv=FAKE, parent=FAKE, kn=None, vn=None,
+             slopes=None, anc=None, ws=FAKE, ws_bytes=0)
+    a.update(kw)
+    return lib.segkv_sdpa_decode(a["out"], a["q"], a["pk"], a["pv"], a["rk"], a["rv"], a["parent"],
+                                 a["kn"], a["vn"], a["slopes"], a["anc"], a["ws"], a["ws_bytes"],
+                                 0.125, ctypes.byref(dims), None)
+
+
+def test_decode_rejects_bad_arguments_without_a_device():
+    good = dict(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=64, T=5, Tcap=16)
+    d = segkv.make_dims(**good)
+    assert _decode(d, out=None) == binding.SEGKV_INVALID_ARG
+    assert _decode(d, pk=None) == binding.SEGKV_INVALID_ARG
+    assert _decode(d, parent=None) == binding.SEGKV_INVALID_ARG
+    assert _decode(d, kn=FAKE) == binding.SEGKV_INVALID_ARG            # only one of the pair
+    assert _decode(d, q=FAKE + 8) == binding.SEGKV_MISALIGNED
+    assert _decode(d, rk=FAKE + 2) == binding.SEGKV_MISALIGNED
+    for bad in (dict(T=0), dict(T=17), dict(Hq=7), dict(B=0), dict(Lp=-1), dict(beam=0)):
+        assert _decode(segkv.make_dims(**{**good, **bad})) == binding.SEGKV_INVALID_ARG
+    for bad in (dict(D=96), dict(beam=9), dict(D=512)):
+        assert _decode(segkv.make_dims(**{**good, **bad})) == binding.SEGKV_UNSUPPORTED
+
+
+def test_workspace_requirement_is_enforced(monkeypatch):
+    monkeypatch.setenv("SEGKV_TARGET_GROUPS", str(1 << 20))    # force split-KV
+    d = segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=512, T=5, Tcap=16)
+    need = segkv.workspace_bytes(d)
+    assert need > 0 and need % 16 == 0
+    assert _decode(d, ws=FAKE, ws_bytes=need - 1) == binding.SEGKV_WORKSPACE_TOO_SMALL
+    assert _decode(d, ws=None, ws_bytes=need) == binding.SEGKV_WORKSPACE_TOO_SMALL
+    assert segkv.workspace_bytes(segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=96, Lp=512, T=5,
+                                                 Tcap=16)) == 0
+
+
+def test_append_rejects_bad_arguments_without_a_device():
+    lib = segkv.load_library()
+    d = segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=64, T=5, Tcap=16)
+    call = lambda rk, t: lib.segkv_append_kv(rk, FAKE, FAKE, FAKE, t, ctypes.byref(d), None)
+    assert call(None, 0) == binding.SEGKV_INVALID_ARG
+    assert call(FAKE, -1) == binding.SEGKV_INVALID_ARG
+    assert call(FAKE, 16) == binding.SEGKV_INVALID_ARG
+    assert call(FAKE + 4, 3) == binding.SEGKV_MISALIGNED
+
+
+def test_probe_rejects_bad_arguments_without_a_device():
+    lib = segkv.load_library()
+    assert lib.segkv_stream_read_probe(None, 1024, FAKE, None) == binding.SEGKV_INVALID_ARG
+    assert lib.segkv_stream_read_probe(FAKE, 1000, FAKE, None) == binding.SEGKV_INVALID_ARG
+    assert lib.segkv_stream_read_probe(FAKE + 4, 1024, FAKE, None) == binding.SEGKV_MISALIGNED
