@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused segment-KV decode attention on one MI355X.
+
+A "step" is one pass of the whole hot path for one decoder layer over one batch:
+a single segkv_sdpa_decode call with fused append (row copy, ancestor
+resolution, prompt + response attention, split-KV merge).  Inputs are synthetic
+fp16 N(0,1) tensors of the benchmark shapes, resident in HBM before timing.  To
+keep every launch HBM-cold the timed loop cycles through several independent
+buffer sets ("layers") whose total footprint exceeds 4x the 256 MB Infinity
+Cache, as a real model cycles through its layers' caches.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+MALL_BYTES = 256 << 20
+
+
+def algorithmic_bytes(wl, unique_rows: int) -> dict:
+    """Bytes one layer-step must move: prompt K/V once per request, the distinct
+    response rows referenced, Q read + O write, append read + write, parent table."""
+    row = wl.Hkv * wl.D * 2
+    qo = 2 * wl.N * wl.Hq * wl.D * 2
+    fixed = 2 * wl.B * wl.Lp * row + qo + 4 * wl.N * row + wl.T * wl.N * 4
+    return {"unique": fixed + 2 * unique_rows * row,
+            "nominal": fixed + 2 * wl.T * wl.N * row}
+
+
+class DeviceSet:
+    """One independent set of operands on the GPU (one "layer")."""
+
+    def __init__(self, wl, seed, parent_np, slopes_np, segkv, torch):
+        dev = torch.device("cuda:0")
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+
+        def rnd(*shape):
+            return torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).half()
+
+        self.q = rnd(wl.N, wl.Hq, wl.D)
+        self.pk = rnd(wl.B, wl.Lp, wl.Hkv, wl.D)
+        self.pv = rnd(wl.B, wl.Lp, wl.Hkv, wl.D)
+        self.rk = torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16, device=dev)
+        self.rv = torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16, device=dev)
+        if wl.T > 1:
+            self.rk[: wl.T - 1] = rnd(wl.T - 1, wl.N, wl.Hkv, wl.D)
+            self.rv[: wl.T - 1] = rnd(wl.T - 1, wl.N, wl.Hkv, wl.D)
+        self.kn = rnd(wl.N, wl.Hkv, wl.D)
+        self.vn = rnd(wl.N, wl.Hkv, wl.D)
+        self.parent = torch.from_numpy(parent_np).to(dev)
+        self.slopes = None if slopes_np is None else torch.from_numpy(slopes_np).to(dev)
+        self.out = torch.empty(wl.N, wl.Hq, wl.D, dtype=torch.float16, device=dev)
+        self.dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+        nb = segkv.workspace_bytes(self.dims)
+        self.ws = torch.empty(max(nb, 16) // 4, dtype=torch.float32, device=dev) if nb else None
+        self.call = segkv.prepare_sdpa_decode(self.out, self.q, self.pk, self.pv, self.rk, self.rv,
+                                              self.parent, self.dims, wl.scale, k_new=self.kn,
+                                              v_new=self.vn, alibi_slopes=self.slopes,
+                                              workspace=self.ws)
+
+    def to_numpy(self):
+        c = lambda t: None if t is None else t.cpu().numpy()
+        return {"q": c(self.q), "prompt_k": c(self.pk), "prompt_v": c(self.pv), "resp_k": c(self.rk),
+                "resp_v": c(self.rv), "k_new": c(self.kn), "v_new": c(self.vn),
+                "parent": c(self.parent), "slopes": c(self.slopes)}
+
+
+def unique_rows_from_anc(anc, wl):
+    import numpy as np
+    offs = (np.arange(wl.N) // wl.W) * wl.W
+    return int(sum(np.unique(offs + anc[s]).size for s in range(wl.T)))
+
+
+def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_seconds):
+    import numpy as np
+    from paper_2401_05391_amd.workloads import alibi_slopes, make_parent
+
+    rng = np.random.default_rng(wl.seed)
+    parent_np = make_parent(wl, rng)
+    slopes_np = alibi_slopes(wl.Hq) if wl.alibi else None
+
+    row = wl.Hkv * wl.D * 2
+    set_bytes = 2 * wl.B * wl.Lp * row + 2 * wl.T * wl.N * row
+    n_sets = max(2, math.ceil(4 * MALL_BYTES / set_bytes))
+    sets = [DeviceSet(wl, 1000 * wl.seed + i, parent_np, slopes_np, segkv, torch) for i in range(n_sets)]
+    torch.cuda.synchronize()
+
+    # resolved ancestors as the kernel used them -> distinct response rows referenced
+    anc = torch.empty(wl.T, wl.N, dtype=torch.int32, device="cuda:0")
+    s0 = sets[0]
+    cpu_inputs = s0.to_numpy() if want_cpu_baseline else None
+    segkv.sdpa_decode(s0.out, s0.q, s0.pk, s0.pv, s0.rk, s0.rv, s0.parent, s0.dims, wl.scale,
+                      k_new=s0.kn, v_new=s0.vn, alibi_slopes=s0.slopes, anc_out=anc, workspace=s0.ws)
+    torch.cuda.synchronize()
+    U = unique_rows_from_anc(anc.cpu().numpy(), wl)
+    nbytes = algorithmic_bytes(wl, U)
+
+    for i in range(warmup):
+        sets[i % n_sets].call()
+    torch.cuda.synchronize()
+
+    # (1) whole-job wall clock over exactly `steps` steps
+    t0 = time.perf_counter()
+    for i in range(steps):
+        sets[i % n_sets].call()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / steps
+
+    # (2) per-launch device time with HIP events on the launch stream
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(steps)]
+    for i in range(steps):
+        evs[i][0].record()
+        sets[i % n_sets].call()
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    dev_ms = np.array([a.elapsed_time(b) for a, b in evs])
+
+    # (3) practical streaming-read ceiling: same bytes, pure 128-bit loads
+    sink = torch.empty(4096, dtype=torch.int32, device="cuda:0")
+    probe_src = [torch.cat([s.pk.view(-1), s.pv.view(-1)]) for s in sets[:2]]
+    for i in range(3):
+        segkv.stream_read_probe(probe_src[i % 2], sink)
+    pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    for i in range(10):
+        pe[i][0].record()
+        segkv.stream_read_probe(probe_src[i % 2], sink)
+        pe[i][1].record()
+    torch.cuda.synchronize()
+    probe_ms = float(np.median([a.elapsed_time(b) for a, b in pe]))
+    probe_gbs = probe_src[0].numel() * 2 / (probe_ms * 1e-3) / 1e9
+    del probe_src
+
+    res = {
+        "workload": wl.name,
+        "shape": {"B": wl.B, "beam": wl.W, "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "Lp": wl.Lp,
+                  "T": wl.T, "alibi": wl.alibi},
+        "buffer_sets": n_sets,
+        "unique_response_rows": U,
+        "bytes_unique": nbytes["unique"], "bytes_nominal": nbytes["nominal"],
+        "ms_per_step": ms_per_step,
+        "us_per_layer_step": ms_per_step * 1e3,
+        "gbs_unique": nbytes["unique"] / (ms_per_step * 1e-3) / 1e9,
+        "gbs_nominal": nbytes["nominal"] / (ms_per_step * 1e-3) / 1e9,
+        "device_us": {"mean": float(dev_ms.mean() * 1e3), "median": float(np.median(dev_ms) * 1e3),
+                      "min": float(dev_ms.min() * 1e3), "p90": float(np.percentile(dev_ms, 90) * 1e3)},
+        "stream_read_probe_gbs": probe_gbs,
+        "workspace_bytes": segkv.workspace_bytes(s0.dims),
+    }
+    res["roofline"] = {
+        "bound": "hbm", "achieved": nbytes["unique"] / (dev_ms.mean() * 1e-3) / 1e9,
+        "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": nbytes["unique"] / (dev_ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": None,
+    }
+
+    if want_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, cpu_inputs, nbytes["unique"], cpu_seconds, U)
+    del sets
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(wl, x, bytes_unique, budget_s, U):
+    """The fp64 oracle as it stands, timed on this machine's host cores on the first
+    requests of the same batch (a bounded sample), scaled to the metric's unit."""
+    import numpy as np
+    from oracle import segkv_oracle as oracle
+
+    rk, rv = x["resp_k"], x["resp_v"]
+    oracle.append_kv(rk, rv, x["k_new"], x["v_new"], wl.T - 1)
+    per_req = wl.W * wl.Hq
+
+    def run(nreq):
+        pairs = np.array([(n, h) for n in range(nreq * wl.W) for h in range(wl.Hq)], dtype=np.int32)
+        t0 = time.perf_counter()
+        oracle.sdpa_decode(x["q"], x["prompt_k"], x["prompt_v"], rk, rv, x["parent"], wl.W, wl.T,
+                           wl.scale, slopes=x["slopes"], pairs=pairs)
+        return time.perf_counter() - t0
+
+    t1 = run(1)                                   # calibrate on one request
+    nreq = int(max(1, min(wl.B, budget_s / max(t1, 1e-4))))
+    t = run(nreq)
+    frac = nreq / wl.B
+    return {"value": bytes_unique * frac / t / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"first {nreq} of {wl.B} requests ({nreq * per_req} of {wl.B * per_req} "
+                      f"query rows), {t:.2f} s wall",
+            "ms_per_step_extrapolated": t / frac * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama2_7b_greedy")
+    ap.add_argument("--others", default="llama2_70b_gqa,gptj6b,bloom176b_alibi",
+                    help="comma list of further workloads reported under other_workloads ('' = none)")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2401_05391_amd as segkv
+    from paper_2401_05391_amd.workloads import CONFIGS
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    segkv.load_library()
+
+    wl = CONFIGS[a.workload]
+    main_res = time_workload(wl, a.steps, a.warmup, segkv, torch, not a.no_cpu_baseline, a.cpu_seconds)
+    others = []
+    for name in [n for n in a.others.split(",") if n and n != a.workload]:
+        others.append(time_workload(CONFIGS[name], a.steps, a.warmup, segkv, torch, False, 0))
+
+    line = {
+        "metric": "fused segment-KV decode SDPA: achieved HBM GB/s (us/layer-step in us_per_layer_step)",
+        "value": main_res["gbs_unique"], "unit": "GB/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": main_res["ms_per_step"], "us_per_layer_step": main_res["us_per_layer_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": wl.name, **main_res["shape"], "append": "fused",
+                   "buffer_sets": main_res["buffer_sets"]},
+        "pct_of_hbm_peak": 100.0 * main_res["gbs_unique"] / HBM_PEAK_GBS,
+        "roofline": main_res["roofline"],
+        "cpu_baseline": main_res.get("cpu_baseline"),
+        "detail": {k: main_res[k] for k in ("bytes_unique", "bytes_nominal", "unique_response_rows",
+                                            "gbs_nominal", "device_us", "stream_read_probe_gbs",
+                                            "workspace_bytes")},
+        "other_workloads": [{k: r[k] for k in ("workload", "shape", "us_per_layer_step", "gbs_unique",
+                                               "gbs_nominal", "bytes_unique", "device_us", "roofline",
+                                               "stream_read_probe_gbs", "buffer_sets")}
+                            for r in others],
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

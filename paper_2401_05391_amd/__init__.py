@@ -6,4 +6,4 @@ The library is loaded on first use of an entry point, not at import.
 """
 from . import binding, build, workloads  # noqa: F401
 from .binding import (SegkvDims, SegkvError, append_kv, load_library, make_dims,  # noqa: F401
-                      sdpa_decode, status_string, stream_read_probe, workspace_bytes)
+                      prepare_sdpa_decode, sdpa_decode, status_string, stream_read_probe, workspace_bytes)

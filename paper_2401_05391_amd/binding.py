@@ -108,6 +108,27 @@ def sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvD
         raise SegkvError(rc, "segkv_sdpa_decode")
 
 
+def prepare_sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvDims,
+                        scale: float, k_new=None, v_new=None, alibi_slopes=None, anc_out=None,
+                        workspace=None, stream=None):
+    """Marshal the arguments once; returns a zero-argument callable that enqueues
+    the same segkv_sdpa_decode call each time (for launch loops where per-call
+    Python marshalling would rival the kernel time).  The tensors must stay alive."""
+    fn = load_library().segkv_sdpa_decode
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    vp = ctypes.c_void_p
+    args = ([vp(_ptr(t)) for t in (out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new,
+                                   v_new, alibi_slopes, anc_out, workspace)]
+            + [ctypes.c_size_t(ws_bytes), ctypes.c_float(scale), ctypes.byref(dims),
+               vp(_stream_handle(stream))])
+
+    def call() -> None:
+        rc = fn(*args)
+        if rc != SEGKV_OK:
+            raise SegkvError(rc, "segkv_sdpa_decode")
+    return call
+
+
 def stream_read_probe(src, sink, stream=None) -> None:
     nbytes = (src.numel() * src.element_size()) // 16 * 16
     rc = load_library().segkv_stream_read_probe(_ptr(src), nbytes, _ptr(sink),
