@@ -12,6 +12,7 @@ using segkv::SdpaParams;
 
 struct Plan {
     int G, nq, QB, n_qblocks;
+    int HP;   // adjacent KV heads handled by one wave-wide load
     int merged, n_chunks, pchunk, rchunk, n_rchunks, n_pchunks;
     size_t ws_ml_bytes, ws_acc_bytes;
     unsigned grid;
@@ -49,8 +50,10 @@ Plan make_plan(const segkv_dims* d)
     pl.nq = d->beam * pl.G;
     pl.QB = (pl.nq == 1) ? 1 : 4;
     pl.n_qblocks = ceil_div(pl.nq, pl.QB);
-    const long units = (long)d->B * d->Hkv * pl.n_qblocks;
-    const int target_groups = env_int("SEGKV_TARGET_GROUPS", 2048);
+    pl.HP = env_int("SEGKV_HEADS_PER_WAVE", 4);
+    while (pl.HP > 1 && (d->Hkv % pl.HP != 0 || (pl.HP != 1 && pl.HP != 2 && pl.HP != 4))) pl.HP >>= 1;
+    const long units = (long)d->B * (d->Hkv / pl.HP) * pl.n_qblocks;
+    const int target_groups = env_int("SEGKV_TARGET_GROUPS", 1024);
     const int min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * pl.QB);
 
     if (d->T <= segkv::kMaxStepsPerChunk && units >= target_groups) {
@@ -176,7 +179,7 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
     p.n_rchunks = pl.n_rchunks;
 
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.grid, st);
+    hipError_t e = segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.HP, pl.grid, st);
     if (e != hipSuccess) return SEGKV_HIP_ERROR;
     if (pl.n_chunks > 1) {
         e = segkv::launch_sdpa_merge(p.out, p.ws_ml, p.ws_acc, d->B * d->beam * d->Hq, d->D,

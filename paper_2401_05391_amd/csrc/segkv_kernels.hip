@@ -26,13 +26,19 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 static_assert(kMaxStepsPerChunk == kThreads, "one thread per response step of a chunk");
 
-__device__ __forceinline__ uint4 load16(const _Float16* p)
+__device__ __forceinline__ u32x4_t load16(const _Float16* p)
 {
-    return *reinterpret_cast<const uint4*>(p);
+    return *reinterpret_cast<const u32x4_t*>(p);
 }
-__device__ __forceinline__ void store16(_Float16* p, uint4 v)
+// K/V rows are read exactly once per launch: non-temporal, so they stream past
+// the caches instead of evicting what is reused (Q, parent table, partials).
+__device__ __forceinline__ u32x4_t load16_stream(const _Float16* p)
 {
-    *reinterpret_cast<uint4*>(p) = v;
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+}
+__device__ __forceinline__ void store16(_Float16* p, u32x4_t v)
+{
+    *reinterpret_cast<u32x4_t*>(p) = v;
 }
 __device__ __forceinline__ half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
 
@@ -152,47 +158,94 @@ __device__ void build_response_list(ResponseListSmem& sm, const int32_t* parent,
     __syncthreads();
 }
 
+// Software pipeline over the tiles ti = first, first+kWaves, ... < n_tiles of one
+// wave: the loads of the next tile are issued before the current one is
+// consumed.  Two named buffers alternate (no register copies), and the steady
+// state has no conditional fetch, so the wait before a consume only covers the
+// tile it needs and leaves the newer loads in flight.
+template <class Tile, class Fetch, class Consume>
+__device__ __forceinline__ void stream_tiles_impl(Fetch& fetch, Consume& consume, int first,
+                                                  int n_tiles)
+{
+    if (first >= n_tiles) return;
+    int rem = (n_tiles - first + kWaves - 1) / kWaves;   // tiles of this wave not yet consumed
+    int ti = first;
+    Tile a, b;
+    fetch(a, ti);
+    while (rem >= 3) {
+        fetch(b, ti + kWaves);
+        consume(a);
+        fetch(a, ti + 2 * kWaves);
+        consume(b);
+        ti += 2 * kWaves;
+        rem -= 2;
+    }
+    if (rem == 2) {
+        fetch(b, ti + kWaves);
+        consume(a);
+        consume(b);
+    } else {
+        consume(a);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Main kernel
 // ---------------------------------------------------------------------------
-template <int D>
+// Lane geometry for head dimension D and HP KV heads per wave.  A wave-wide
+// 128-bit load covers NG = 64/LPR row slices of LPR*16 bytes; HP of them are
+// the same key row in HP adjacent KV heads (contiguous in memory, since the
+// head index is the next-to-innermost dimension of every K/V tensor), the
+// remaining factor R = NG/HP are consecutive key rows.
+template <int D, int HP>
 struct Geometry {
-    static constexpr int LPR = (D >= 128) ? 16 : D / 8;   // lanes per key row
+    static constexpr int LPR = (D >= 128) ? 16 : D / 8;   // lanes per row slice
     static constexpr int NV = D / (8 * LPR);              // 16-byte vectors per lane per row
-    static constexpr int R = 64 / LPR;                    // rows per wave-wide load
+    static constexpr int NG = 64 / LPR;                   // lane groups per wave
+    static constexpr int R = NG / HP;                     // key rows per wave-wide load
     static constexpr int U = (NV == 1) ? 4 : 2;           // loads in flight per operand
     static constexpr int EPL = NV * 8;                    // head-dim elements per lane
+    static_assert(NG % HP == 0 && R >= 1, "HP must divide the lane groups of a wave");
 };
 
-template <int D, int QB>
+template <int D, int QB, int HP>
 struct MergeSmem {
-    float ml[kWaves][QB][2];
-    float acc[kWaves][QB][D];
+    float ml[kWaves][HP][QB][2];
+    float acc[kWaves][HP][QB][D];
 };
 
-template <int D, int QB>
-__global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
+template <int D, int QB, int HP>
+union KernelSmem {
+    ResponseListSmem list;
+    MergeSmem<D, QB, HP> merge;
+};
+
+template <int D, int QB, int HP>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3 : 2)))
+void sdpa_decode_alu_kernel(SdpaParams p)
 {
-    using Geo = Geometry<D>;
+    using Geo = Geometry<D, HP>;
     constexpr int LPR = Geo::LPR, NV = Geo::NV, R = Geo::R, U = Geo::U, EPL = Geo::EPL;
     constexpr int TILE = R * U;
 
-    __shared__ ResponseListSmem s_list;
-    __shared__ MergeSmem<D, QB> s_merge;
+    __shared__ KernelSmem<D, QB, HP> smem;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int c = lane % LPR;     // 16-byte column of the row slice
-    const int r = lane / LPR;     // row within a wave-wide load
+    const int c = lane % LPR;            // 16-byte column of the row slice
+    const int grp = lane / LPR;          // lane group
+    const int hl = grp % HP;             // KV head within the block of HP heads
+    const int rl = grp / HP;             // key row within a wave-wide load
 
     // ---- which work item ----
     int id = blockIdx.x;
-    const int qb = id % p.n_qblocks; id /= p.n_qblocks;
-    const int g = id % p.Hkv;        id /= p.Hkv;
+    const int qb = id % p.n_qblocks;     id /= p.n_qblocks;
+    const int gb = id % (p.Hkv / HP);    id /= (p.Hkv / HP);
     const int chunk = id % p.n_chunks;
     const int b = id / p.n_chunks;
     const int N = p.B * p.W;
+    const int g = gb * HP + hl;          // this lane's KV head
 
     // merged: one work-group walks the whole prompt and the whole response;
     // otherwise a chunk is a slice of response steps or of prompt positions.
@@ -209,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
     }
     const bool direct_out = (p.n_chunks == 1);
 
-    // ---- queries of this block ----
+    // ---- queries of this block (Section 3.3: Q is loaded into registers first) ----
     half2_t qv[QB][NV * 4];
     float slope2[QB];
     int qbeam[QB];
@@ -224,7 +277,7 @@ __global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
         slope2[qi] = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            const uint4 w = load16(p.q + qoff + v * (LPR * 8) + c * 8);
+            const u32x4_t w = load16(p.q + qoff + v * (LPR * 8) + c * 8);
             qv[qi][v * 4 + 0] = as_half2(w.x);
             qv[qi][v * 4 + 1] = as_half2(w.y);
             qv[qi][v * 4 + 2] = as_half2(w.z);
@@ -233,18 +286,19 @@ __global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
     }
     const int qpos = p.Lp + p.T - 1;
 
-    // ---- fused append: the block that owns step T-1 copies the unit's new rows ----
+    // ---- fused append: the block that owns step T-1 copies its heads' new rows ----
     const bool have_new = (p.k_new != nullptr);
     if (have_new && qb == 0 && s1 == p.T && s0 < s1) {
-        const int vec_per_row = D / 8;
-        const int total = p.W * vec_per_row * 2;
+        constexpr int kVecPerRow = HP * D / 8;          // HP adjacent heads are contiguous
+        const int total = p.W * kVecPerRow * 2;
         for (int i = tid; i < total; i += kThreads) {
-            const int which = i / (p.W * vec_per_row);
-            const int rem = i % (p.W * vec_per_row);
-            const int u = rem / vec_per_row;
-            const int col = rem % vec_per_row;
-            const size_t src = ((size_t)(b * p.W + u) * p.Hkv + g) * D + col * 8;
-            const size_t dst = (((size_t)(p.T - 1) * N + b * p.W + u) * p.Hkv + g) * D + col * 8;
+            const int which = i / (p.W * kVecPerRow);
+            const int rem = i % (p.W * kVecPerRow);
+            const int u = rem / kVecPerRow;
+            const int col = rem % kVecPerRow;
+            const size_t src = ((size_t)(b * p.W + u) * p.Hkv + gb * HP) * D + col * 8;
+            const size_t dst =
+                (((size_t)(p.T - 1) * N + b * p.W + u) * p.Hkv + gb * HP) * D + col * 8;
             if (which == 0) store16(p.resp_k + dst, load16(p.k_new + src));
             else            store16(p.resp_v + dst, load16(p.v_new + src));
         }
@@ -261,8 +315,8 @@ __global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
     }
 
     struct Tile {
-        uint4 k[U][NV];
-        uint4 v[U][NV];
+        u32x4_t k[U][NV];
+        u32x4_t v[U][NV];
         int kpos[U];
         uint32_t bmask[U];   // beams that see the row; 0 = row not valid
     };
@@ -322,43 +376,34 @@ __global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
         auto fetch = [&](Tile& t, int ti) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = k0 + ti * TILE + u * R + r;
+                const int i = k0 + ti * TILE + u * R + rl;
                 const bool ok = i < k1;
                 const int ic = ok ? i : (k1 - 1);
                 const size_t off = (((size_t)b * p.Lp + ic) * p.Hkv + g) * D + c * 8;
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
-                    t.k[u][v] = load16(p.prompt_k + off + v * (LPR * 8));
-                    t.v[u][v] = load16(p.prompt_v + off + v * (LPR * 8));
+                    t.k[u][v] = load16_stream(p.prompt_k + off + v * (LPR * 8));
+                    t.v[u][v] = load16_stream(p.prompt_v + off + v * (LPR * 8));
                 }
                 t.kpos[u] = ic;
                 t.bmask[u] = ok ? 0xffu : 0u;
             }
         };
-        Tile cur, nxt;
-        int ti = wave;
-        if (ti < n_tiles) fetch(cur, ti);
-        for (; ti < n_tiles; ti += kWaves) {
-            const bool more = (ti + kWaves) < n_tiles;
-            if (more) fetch(nxt, ti + kWaves);
-            consume(cur);
-            if (more) cur = nxt;
-        }
+        stream_tiles_impl<Tile>(fetch, consume, wave, n_tiles);
     }
 
     // ---- response segment (index select fused: rows chosen by the beam lineage) ----
     if (s1 > s0) {
-        build_response_list(s_list, p.parent,
-                            (g == 0 && qb == 0) ? p.anc_out : nullptr,
+        build_response_list(smem.list, p.parent, (gb == 0 && qb == 0) ? p.anc_out : nullptr,
                             p.B, p.W, p.T, b, s0, s1);
-        const int total = s_list.total;
+        const int total = smem.list.total;
         const int n_tiles = (total + TILE - 1) / TILE;
         auto fetch = [&](Tile& t, int ti) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int e = ti * TILE + u * R + r;
+                const int e = ti * TILE + u * R + rl;
                 const bool ok = e < total;
-                const uint32_t ent = s_list.ent[ok ? e : (total - 1)];
+                const uint32_t ent = smem.list.ent[ok ? e : (total - 1)];
                 const int s = s0 + (int)(ent >> 16);
                 const int slot = (int)((ent >> 8) & 0xffu);
                 const _Float16* kp;
@@ -374,27 +419,19 @@ __global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
                 }
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
-                    t.k[u][v] = load16(kp + v * (LPR * 8));
-                    t.v[u][v] = load16(vp + v * (LPR * 8));
+                    t.k[u][v] = load16_stream(kp + v * (LPR * 8));
+                    t.v[u][v] = load16_stream(vp + v * (LPR * 8));
                 }
                 t.kpos[u] = p.Lp + s;
                 t.bmask[u] = ok ? (ent & 0xffu) : 0u;
             }
         };
-        Tile cur, nxt;
-        int ti = wave;
-        if (ti < n_tiles) fetch(cur, ti);
-        for (; ti < n_tiles; ti += kWaves) {
-            const bool more = (ti + kWaves) < n_tiles;
-            if (more) fetch(nxt, ti + kWaves);
-            consume(cur);
-            if (more) cur = nxt;
-        }
+        stream_tiles_impl<Tile>(fetch, consume, wave, n_tiles);
     }
 
-    // ---- merge lane groups of the wave (butterfly over the row index) ----
+    // ---- merge the lane groups that hold different rows of the same head ----
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
+    for (int off = LPR * HP; off < 64; off <<= 1) {
 #pragma unroll
         for (int qi = 0; qi < QB; ++qi) {
             const float mo = __shfl_xor(m[qi], off);
@@ -412,41 +449,43 @@ __global__ __launch_bounds__(kThreads) void sdpa_decode_alu_kernel(SdpaParams p)
         }
     }
 
-    // ---- merge the waves through LDS ----
-    if (r == 0) {
+    // ---- merge the waves through LDS (reuses the response-list storage) ----
+    __syncthreads();
+    if (rl == 0) {
 #pragma unroll
         for (int qi = 0; qi < QB; ++qi) {
             if (c == 0) {
-                s_merge.ml[wave][qi][0] = m[qi];
-                s_merge.ml[wave][qi][1] = l[qi];
+                smem.merge.ml[wave][hl][qi][0] = m[qi];
+                smem.merge.ml[wave][hl][qi][1] = l[qi];
             }
 #pragma unroll
             for (int v = 0; v < NV; ++v)
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    s_merge.acc[wave][qi][v * (LPR * 8) + c * 8 + e] = acc[qi][v * 8 + e];
+                    smem.merge.acc[wave][hl][qi][v * (LPR * 8) + c * 8 + e] = acc[qi][v * 8 + e];
         }
     }
     __syncthreads();
 
     const int NQ = N * p.Hq;
-    for (int idx = tid; idx < QB * D; idx += kThreads) {
-        const int qi = idx / D;
+    for (int idx = tid; idx < HP * QB * D; idx += kThreads) {
         const int d = idx % D;
-        if (qb * QB + qi >= p.nq) continue;
-        float mm = s_merge.ml[0][qi][0];
+        const int qi = (idx / D) % QB;
+        const int h = idx / (D * QB);
+        const int lq = qb * QB + qi;
+        if (lq >= p.nq) continue;
+        float mm = smem.merge.ml[0][h][qi][0];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, s_merge.ml[w][qi][0]);
+        for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, smem.merge.ml[w][h][qi][0]);
         float ll = 0.0f, aa = 0.0f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            const float f = fast_exp2(s_merge.ml[w][qi][0] - mm);
-            ll += s_merge.ml[w][qi][1] * f;
-            aa += s_merge.acc[w][qi][d] * f;
+            const float f = fast_exp2(smem.merge.ml[w][h][qi][0] - mm);
+            ll += smem.merge.ml[w][h][qi][1] * f;
+            aa += smem.merge.acc[w][h][qi][d] * f;
         }
-        const int lq = qb * QB + qi;
         const int j = lq / p.G;
-        const int hq = g * p.G + (lq % p.G);
+        const int hq = (gb * HP + h) * p.G + (lq % p.G);
         const size_t qidx = (size_t)(b * p.W + j) * p.Hq + hq;
         if (direct_out) {
             p.out[qidx * D + d] = (_Float16)(aa / ll);
@@ -513,24 +552,28 @@ __global__ __launch_bounds__(256) void append_kv_kernel(uint4* __restrict__ dst_
 }
 
 // ---------------------------------------------------------------------------
-// Streaming-read probe: the practical HBM read ceiling for this access shape.
+// Streaming-read probe: the practical HBM read ceiling.  Every work-group
+// sweeps its own contiguous slice with eight non-temporal 128-bit loads in
+// flight per lane -- the friendliest shape this device has for a pure read.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void stream_read_probe_kernel(const uint4* __restrict__ src,
+__global__ __launch_bounds__(256) void stream_read_probe_kernel(const u32x4_t* __restrict__ src,
                                                                 size_t n_vec, uint32_t* sink)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    constexpr int kInFlight = 8;
+    const size_t per_group = (n_vec + gridDim.x - 1) / gridDim.x;
+    const size_t lo = (size_t)blockIdx.x * per_group;
+    const size_t hi = lo + per_group < n_vec ? lo + per_group : n_vec;
     uint32_t x = 0;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n_vec; i += 4 * stride) {
-        const uint4 a = src[i];
-        const uint4 b = src[i + stride];
-        const uint4 c = src[i + 2 * stride];
-        const uint4 d = src[i + 3 * stride];
-        x ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w;
-        x ^= c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    size_t i = lo + threadIdx.x;
+    for (; i + (kInFlight - 1) * 256 < hi; i += kInFlight * 256) {
+        u32x4_t v[kInFlight];
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
-    for (; i < n_vec; i += stride) {
-        const uint4 a = src[i];
+    for (; i < hi; i += 256) {
+        const u32x4_t a = __builtin_nontemporal_load(src + i);
         x ^= a.x ^ a.y ^ a.z ^ a.w;
     }
     // one word per work-group; the xor keeps every load live
@@ -547,20 +590,32 @@ __global__ __launch_bounds__(256) void stream_read_probe_kernel(const uint4* __r
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
-template <int D>
-static hipError_t launch_sdpa_d(const SdpaParams& p, int QB, unsigned grid, hipStream_t st)
+template <int D, int QB, int HP>
+static hipError_t launch_one(const SdpaParams& p, unsigned grid, hipStream_t st)
 {
-    if (QB == 1) hipLaunchKernelGGL((sdpa_decode_alu_kernel<D, 1>), dim3(grid), dim3(kThreads), 0, st, p);
-    else         hipLaunchKernelGGL((sdpa_decode_alu_kernel<D, 4>), dim3(grid), dim3(kThreads), 0, st, p);
+    hipLaunchKernelGGL((sdpa_decode_alu_kernel<D, QB, HP>), dim3(grid), dim3(kThreads), 0, st, p);
     return hipGetLastError();
 }
 
-hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, unsigned grid, hipStream_t st)
+template <int D, int QB>
+static hipError_t launch_hp(const SdpaParams& p, int HP, unsigned grid, hipStream_t st)
 {
+    switch (HP) {
+        case 1: return launch_one<D, QB, 1>(p, grid, st);
+        case 2: return launch_one<D, QB, 2>(p, grid, st);
+        case 4: return launch_one<D, QB, 4>(p, grid, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, int HP, unsigned grid,
+                              hipStream_t st)
+{
+    if (QB != 1 && QB != 4) return hipErrorInvalidValue;
     switch (D) {
-        case 64:  return launch_sdpa_d<64>(p, QB, grid, st);
-        case 128: return launch_sdpa_d<128>(p, QB, grid, st);
-        case 256: return launch_sdpa_d<256>(p, QB, grid, st);
+        case 64:  return QB == 1 ? launch_hp<64, 1>(p, HP, grid, st) : launch_hp<64, 4>(p, HP, grid, st);
+        case 128: return QB == 1 ? launch_hp<128, 1>(p, HP, grid, st) : launch_hp<128, 4>(p, HP, grid, st);
+        case 256: return QB == 1 ? launch_hp<256, 1>(p, HP, grid, st) : launch_hp<256, 4>(p, HP, grid, st);
         default:  return hipErrorInvalidValue;
     }
 }
@@ -590,7 +645,7 @@ hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const v
 hipError_t launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st)
 {
     hipLaunchKernelGGL(stream_read_probe_kernel, dim3(kProbeGroups), dim3(256), 0, st,
-                       (const uint4*)src, bytes / 16, (uint32_t*)sink);
+                       (const u32x4_t*)src, bytes / 16, (uint32_t*)sink);
     return hipGetLastError();
 }
 
