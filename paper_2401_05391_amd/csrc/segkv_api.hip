@@ -12,7 +12,8 @@ using segkv::SdpaParams;
 
 struct Plan {
     int G, nq, QB, n_qblocks;
-    int HP;   // adjacent KV heads handled by one wave-wide load
+    int HP;   // adjacent KV heads handled by one wave-wide load (ALU path)
+    int mfma; // 1: matrix-core kernel, 0: vector-ALU kernel
     int merged, n_chunks, pchunk, rchunk, n_rchunks, n_pchunks;
     size_t ws_ml_bytes, ws_acc_bytes;
     unsigned grid;
@@ -39,22 +40,41 @@ bool dims_supported(const segkv_dims* d)
     return (d->D == 64 || d->D == 128 || d->D == 256) && d->beam <= 8;
 }
 
+// Which kernel: the matrix-core path as soon as two or more queries share each
+// K/V row (beams and/or grouped query heads), the vector-ALU path for a single
+// query per row.  SEGKV_PATH=alu|mfma overrides (for A/B measurements).
+bool want_mfma(int nq)
+{
+    const char* s = std::getenv("SEGKV_PATH");
+    if (s && s[0] == 'a') return false;
+    if (s && s[0] == 'm') return true;
+    return nq >= 2;
+}
+
 // How the keys of one (request, KV head) unit are cut into work-groups.
-// Enough work-groups to occupy 256 CUs several times over, but chunks long
-// enough that the fp32 partials written per chunk stay small next to the K/V
-// bytes the chunk reads.
+// Enough work-groups to occupy 256 CUs, but chunks long enough that the fp32
+// partials written per chunk stay small next to the K/V bytes the chunk reads.
 Plan make_plan(const segkv_dims* d)
 {
     Plan pl{};
     pl.G = d->Hq / d->Hkv;
     pl.nq = d->beam * pl.G;
-    pl.QB = (pl.nq == 1) ? 1 : 4;
+    pl.mfma = want_mfma(pl.nq) ? 1 : 0;
+    int target_groups, min_pchunk;
+    if (pl.mfma) {
+        pl.QB = 32;
+        pl.HP = 1;
+        target_groups = env_int("SEGKV_TARGET_GROUPS", 512);
+        min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * (pl.nq < 32 ? pl.nq : 32));
+    } else {
+        pl.QB = (pl.nq == 1) ? 1 : 4;
+        pl.HP = env_int("SEGKV_HEADS_PER_WAVE", 4);
+        while (pl.HP > 1 && (d->Hkv % pl.HP != 0 || (pl.HP != 2 && pl.HP != 4))) pl.HP >>= 1;
+        target_groups = env_int("SEGKV_TARGET_GROUPS", 1024);
+        min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * pl.QB);
+    }
     pl.n_qblocks = ceil_div(pl.nq, pl.QB);
-    pl.HP = env_int("SEGKV_HEADS_PER_WAVE", 4);
-    while (pl.HP > 1 && (d->Hkv % pl.HP != 0 || (pl.HP != 1 && pl.HP != 2 && pl.HP != 4))) pl.HP >>= 1;
     const long units = (long)d->B * (d->Hkv / pl.HP) * pl.n_qblocks;
-    const int target_groups = env_int("SEGKV_TARGET_GROUPS", 1024);
-    const int min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * pl.QB);
 
     if (d->T <= segkv::kMaxStepsPerChunk && units >= target_groups) {
         pl.merged = 1;
@@ -179,7 +199,8 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
     p.n_rchunks = pl.n_rchunks;
 
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.HP, pl.grid, st);
+    hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, d->D, pl.grid, st)
+                           : segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.HP, pl.grid, st);
     if (e != hipSuccess) return SEGKV_HIP_ERROR;
     if (pl.n_chunks > 1) {
         e = segkv::launch_sdpa_merge(p.out, p.ws_ml, p.ws_acc, d->B * d->beam * d->Hq, d->D,
