@@ -40,15 +40,16 @@ bool dims_supported(const segkv_dims* d)
     return (d->D == 64 || d->D == 128 || d->D == 256) && d->beam <= 8;
 }
 
-// Which kernel: the matrix-core path as soon as two or more queries share each
-// K/V row (beams and/or grouped query heads), the vector-ALU path for a single
-// query per row.  SEGKV_PATH=alu|mfma overrides (for A/B measurements).
+// Which kernel: the matrix-core path when more than 4 queries share each K/V
+// row (beams and/or grouped query heads), the vector-ALU path (which takes up
+// to 4 queries per work-group and reads 1 KB-contiguous pieces across adjacent
+// heads) otherwise.  SEGKV_PATH=alu|mfma overrides (for A/B measurements).
 bool want_mfma(int nq)
 {
     const char* s = std::getenv("SEGKV_PATH");
     if (s && s[0] == 'a') return false;
     if (s && s[0] == 'm') return true;
-    return nq >= 2;
+    return nq > 4;
 }
 
 // How the keys of one (request, KV head) unit are cut into work-groups.
@@ -64,7 +65,7 @@ Plan make_plan(const segkv_dims* d)
     if (pl.mfma) {
         pl.QB = 32;
         pl.HP = 1;
-        target_groups = env_int("SEGKV_TARGET_GROUPS", 512);
+        target_groups = env_int("SEGKV_TARGET_GROUPS", 256);
         min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * (pl.nq < 32 ? pl.nq : 32));
     } else {
         pl.QB = (pl.nq == 1) ? 1 : 4;
@@ -76,7 +77,12 @@ Plan make_plan(const segkv_dims* d)
     pl.n_qblocks = ceil_div(pl.nq, pl.QB);
     const long units = (long)d->B * (d->Hkv / pl.HP) * pl.n_qblocks;
 
-    if (d->T <= segkv::kMaxStepsPerChunk && units >= target_groups) {
+    // response steps one work-group may own: one list thread per step, and at
+    // most kMaxListEntries (step, slot) rows
+    int max_steps = segkv::kMaxListEntries / d->beam;
+    if (max_steps > segkv::kMaxStepsPerChunk) max_steps = segkv::kMaxStepsPerChunk;
+
+    if (d->T <= max_steps && units >= target_groups) {
         pl.merged = 1;
         pl.n_chunks = 1;
         pl.n_rchunks = 1;
@@ -85,7 +91,7 @@ Plan make_plan(const segkv_dims* d)
         pl.pchunk = d->Lp > 0 ? d->Lp : 1;
     } else {
         pl.merged = 0;
-        pl.n_rchunks = ceil_div(d->T, segkv::kMaxStepsPerChunk);
+        pl.n_rchunks = ceil_div(d->T, max_steps);
         pl.rchunk = ceil_div(d->T, pl.n_rchunks);
         if (d->Lp > 0) {
             long want = (target_groups + units - 1) / units - pl.n_rchunks;
@@ -197,6 +203,9 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
     p.pchunk = pl.pchunk;
     p.rchunk = pl.rchunk;
     p.n_rchunks = pl.n_rchunks;
+#ifdef SEGKV_TIMING
+    p.timing = (unsigned long long*)std::getenv("SEGKV_TIMING_PTR") ? (unsigned long long*)std::strtoull(std::getenv("SEGKV_TIMING_PTR"), nullptr, 0) : nullptr;
+#endif
 
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, d->D, pl.grid, st)

@@ -12,6 +12,21 @@ namespace segkv {
 // barriers.
 constexpr int kListThreads = kMaxStepsPerChunk;
 
+// Work-groups are handed to the 8 XCDs round-robin (group i runs on XCD i % 8).
+// Remap the hardware index so that each XCD works through one contiguous run of
+// logical work items: neighbours in memory (the KV heads of one request, the
+// chunks of one unit) then share an XCD and its L2, and every XCD sweeps whole
+// rows instead of one fixed 256-byte column of them.
+constexpr int kNumXcd = 8;
+__device__ __forceinline__ int xcd_contiguous_index(int id, int n)
+{
+    const int xcd = id % kNumXcd;
+    const int k = id / kNumXcd;
+    const int per = n / kNumXcd;
+    const int rem = n % kNumXcd;
+    return xcd * per + min(xcd, rem) + k;
+}
+
 __device__ __forceinline__ u32x4_t load16(const _Float16* p)
 {
     return *reinterpret_cast<const u32x4_t*>(p);
@@ -38,32 +53,70 @@ __device__ __forceinline__ half2_t as_half2(uint32_t w) { return __builtin_bit_c
 // for every distinct row referenced, ordered by step.  All threads must call.
 // ---------------------------------------------------------------------------
 struct ResponseListSmem {
-    uint32_t map[2][kListThreads];
-    int cnt[2][kListThreads];
-    uint32_t ent[kListThreads * 8];
+    uint32_t map[kListThreads];        // ordered tree reduction (steps after the chunk)
+    uint32_t wave_map[kListThreads / 64];
+    int wave_cnt[kListThreads / 64];
+    uint32_t ent[kMaxListEntries];
     int total;
 };
 
-__device__ __forceinline__ uint32_t load_parent_map(const int32_t* parent, int N, int W, int b, int s)
+// One step's parent slots of request b, as loaded (not yet packed), so that a
+// kernel can issue these loads early and consume them after other requests
+// have been put in flight.
+struct ParentRow {
+    int32_t v[8];
+};
+
+__device__ __forceinline__ ParentRow load_parent_row(const int32_t* parent, int N, int W, int b, int s)
 {
     const int32_t* row = parent + (size_t)s * N + (size_t)b * W;
-    uint32_t f = kIdentityMap;
-    for (int x = 0; x < W; ++x) {
+    ParentRow r;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) r.v[x] = (x < W) ? row[x] : x;
+    return r;
+}
+
+__device__ __forceinline__ uint32_t pack_parent_row(const ParentRow& r, int W)
+{
+    uint32_t f = 0;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
         // entries are trusted to lie in [0, W); clamping keeps a bad table inside
         // the request's own rows instead of reading past the buffers
-        const uint32_t v = (uint32_t)min(max(row[x], 0), W - 1);
-        f = (f & ~(15u << (4 * x))) | (v << (4 * x));
+        const uint32_t v = (x < W) ? (uint32_t)min(max(r.v[x], 0), W - 1) : (uint32_t)x;
+        f |= v << (4 * x);
     }
     return f;
 }
 
-// Every thread of the work-group must call this (it contains barriers); only
-// threads 0..kListThreads-1 do the work.  Requires blockDim.x >= kListThreads
-// and s1 - s0 <= kListThreads.
-__device__ void build_response_list(ResponseListSmem& sm, const int32_t* parent, int32_t* anc_out,
-                                    int B, int W, int T, int b, int s0, int s1)
+__device__ __forceinline__ uint32_t load_parent_map(const int32_t* parent, int N, int W, int b, int s)
 {
+    return pack_parent_row(load_parent_row(parent, N, W, b, s), W);
+}
+
+// The list thread t of a chunk [s0, s1) owns step s0+t and contributes the
+// parent map of the following step; this issues its loads (nothing for threads
+// without one: identity is substituted when packing).
+__device__ __forceinline__ bool list_thread_has_row(int W, int s0, int s1)
+{
+    return W > 1 && (int)threadIdx.x < (s1 - s0) - 1;
+}
+
+// Every thread of the work-group must call this (it contains barriers); only
+// threads 0..kListThreads-1 do the work.  Requires blockDim.x >= kListThreads,
+// blockDim.x a multiple of 64, and s1 - s0 <= kListThreads.
+// The scans run inside each wave with lane shuffles and are stitched across
+// the kListThreads/64 waves through LDS, so a call costs three barriers (plus
+// the tree reduction when steps follow the chunk).
+// `own_map` is this thread's packed parent map of step s0+t+1 when
+// list_thread_has_row() holds (ignored otherwise).
+__device__ void build_response_list(ResponseListSmem& sm, const int32_t* parent, int32_t* anc_out,
+                                    int B, int W, int T, int b, int s0, int s1, uint32_t own_map)
+{
+    constexpr int kListWaves = kListThreads / 64;
     const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int w = t >> 6;
     const bool active = t < kListThreads;
     const int n = s1 - s0;
     const int N = B * W;
@@ -87,55 +140,53 @@ __device__ void build_response_list(ResponseListSmem& sm, const int32_t* parent,
             const int hi = min(lo + per, T);
             uint32_t c = kIdentityMap;
             for (int s = lo; s < hi; ++s) c = map_compose(c, load_parent_map(parent, N, W, b, s));
-            sm.map[0][t] = c;
+            sm.map[t] = c;
         }
         for (int stride = 1; stride < kListThreads; stride <<= 1) {
             __syncthreads();
             if (active && (t & (2 * stride - 1)) == 0)
-                sm.map[0][t] = map_compose(sm.map[0][t], sm.map[0][t + stride]);
+                sm.map[t] = map_compose(sm.map[t], sm.map[t + stride]);
         }
         __syncthreads();
-        carry = sm.map[0][0];
-        __syncthreads();
+        carry = sm.map[0];
     }
 
     // (2) inclusive suffix scan of y_t = P_{s0+t+1} (t < n-1), y_{n-1} = carry
-    uint32_t y = kIdentityMap;
-    if (t < n - 1) y = load_parent_map(parent, N, W, b, s0 + t + 1);
-    else if (t == n - 1) y = carry;
-    int cur = 0;
-    if (active) sm.map[0][t] = y;
-    __syncthreads();
-    for (int off = 1; off < kListThreads; off <<= 1) {
-        if (active) {
-            uint32_t x = sm.map[cur][t];
-            if (t + off < kListThreads) x = map_compose(x, sm.map[cur][t + off]);
-            sm.map[cur ^ 1][t] = x;
-        }
-        cur ^= 1;
-        __syncthreads();
+    uint32_t x = kIdentityMap;
+    if (t < n - 1) x = own_map;
+    else if (t == n - 1) x = carry;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_down(x, off);
+        if (lane + off < 64) x = map_compose(x, o);
     }
-    const uint32_t A = active ? sm.map[cur][t] : kIdentityMap;   // slot map of step s0+t
+    if (active && lane == 0) sm.wave_map[w] = x;      // composition of the whole wave
+    __syncthreads();
+    if (active)
+        for (int ww = w + 1; ww < kListWaves; ++ww) x = map_compose(x, sm.wave_map[ww]);
+    const uint32_t A = x;                              // slot map of step s0+t
 
     // (3) distinct slots referenced at this step, and their exclusive prefix sum
     uint32_t present = 0;
     if (t < n)
         for (int j = 0; j < W; ++j) present |= 1u << map_get(A, j);
     const int mine = __popc(present);
-    int ccur = 0;
-    if (active) sm.cnt[0][t] = mine;
-    __syncthreads();
-    for (int off = 1; off < kListThreads; off <<= 1) {
-        if (active) {
-            int x = sm.cnt[ccur][t];
-            if (t >= off) x += sm.cnt[ccur][t - off];
-            sm.cnt[ccur ^ 1][t] = x;
-        }
-        ccur ^= 1;
-        __syncthreads();
+    int c = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(c, off);
+        if (lane >= off) c += o;
     }
-    int pos = active ? sm.cnt[ccur][t] - mine : 0;
-    if (t == kListThreads - 1) sm.total = sm.cnt[ccur][t];
+    if (active && lane == 63) sm.wave_cnt[w] = c;
+    __syncthreads();
+    int pos = c - mine;
+    if (active)
+        for (int ww = 0; ww < w; ++ww) pos += sm.wave_cnt[ww];
+    if (t == 0) {
+        int tot = 0;
+        for (int ww = 0; ww < kListWaves; ++ww) tot += sm.wave_cnt[ww];
+        sm.total = tot;
+    }
 
     // (4) entries, and the resolved table if asked for
     if (t < n) {

@@ -108,7 +108,7 @@ void sdpa_decode_alu_kernel(SdpaParams p)
     const int rl = grp / HP;             // key row within a wave-wide load
 
     // ---- which work item ----
-    int id = blockIdx.x;
+    int id = xcd_contiguous_index(blockIdx.x, gridDim.x);
     const int qb = id % p.n_qblocks;     id /= p.n_qblocks;
     const int gb = id % (p.Hkv / HP);    id /= (p.Hkv / HP);
     const int chunk = id % p.n_chunks;
@@ -263,8 +263,11 @@ void sdpa_decode_alu_kernel(SdpaParams p)
 
     // ---- response segment (index select fused: rows chosen by the beam lineage) ----
     if (s1 > s0) {
+        const uint32_t own_map = list_thread_has_row(p.W, s0, s1)
+                                     ? load_parent_map(p.parent, N, p.W, b, s0 + tid + 1)
+                                     : kIdentityMap;
         build_response_list(smem.list, p.parent, (gb == 0 && qb == 0) ? p.anc_out : nullptr,
-                            p.B, p.W, p.T, b, s0, s1);
+                            p.B, p.W, p.T, b, s0, s1, own_map);
         const int total = smem.list.total;
         const int n_tiles = (total + TILE - 1) / TILE;
         auto fetch = [&](Tile& t, int ti) {

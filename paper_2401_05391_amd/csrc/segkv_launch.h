@@ -30,10 +30,14 @@ struct SdpaParams {
     int pchunk;      // prompt positions per chunk
     int rchunk;      // response steps per chunk (<= kMaxStepsPerChunk)
     int n_rchunks;   // response chunks come first in the chunk index
+#ifdef SEGKV_TIMING
+    unsigned long long* timing;   // tuning builds only: per-wave phase timestamps
+#endif
 };
 
 
 constexpr int kMaxStepsPerChunk = 256;   // response steps one work-group can resolve
+constexpr int kMaxListEntries = 1024;    // (step, slot) rows of one chunk: steps * beam <= this
 constexpr int kMfmaWaves64 = 8;           // waves per work-group of the MFMA kernel, by head dim
 constexpr int kMfmaWaves128 = 8;
 constexpr int kMfmaWaves256 = 4;

@@ -20,6 +20,36 @@
 #include "segkv_launch.h"
 #include "segkv_device.h"
 
+// Optional phase timestamps for kernel tuning (compiled in only with
+// -DSEGKV_TIMING; slot k of work-group g, wave w lands in p.timing).
+#ifdef SEGKV_TIMING
+#define SEGKV_STAMP(k)                                                                   \
+    do {                                                                                 \
+        if (p.timing && (threadIdx.x & 63) == 0)                                         \
+            p.timing[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (k)] = wall_clock64(); \
+    } while (0)
+#define SEGKV_PHASE_DECL unsigned long long ph_t = __builtin_readcyclecounter(), ph_acc[4] = {0, 0, 0, 0}
+#define SEGKV_PHASE_BEGIN ph_t = __builtin_readcyclecounter()
+#define SEGKV_PHASE(k)                                       \
+    do {                                                     \
+        const unsigned long long now_ = __builtin_readcyclecounter(); \
+        ph_acc[k] += now_ - ph_t;                            \
+        ph_t = now_;                                         \
+    } while (0)
+#define SEGKV_PHASE_DUMP                                                                   \
+    do {                                                                                   \
+        if (p.timing && (threadIdx.x & 63) == 0)                                           \
+            for (int k_ = 0; k_ < 4; ++k_)                                                 \
+                p.timing[(((size_t)1 << 16) * 16 * 8) + ((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 4 + k_] = ph_acc[k_]; \
+    } while (0)
+#else
+#define SEGKV_STAMP(k) do { } while (0)
+#define SEGKV_PHASE_DECL do { } while (0)
+#define SEGKV_PHASE_BEGIN do { } while (0)
+#define SEGKV_PHASE(k) do { } while (0)
+#define SEGKV_PHASE_DUMP do { } while (0)
+#endif
+
 namespace segkv {
 
 constexpr int kKeyTile = 32;          // keys per MFMA tile (M)
@@ -33,40 +63,56 @@ struct MfmaGeometry {
     static constexpr int NLD = kKeyTile / RPI;        // staging loads per operand per tile
     static constexpr int NKS = D / 16;                // k-steps of the QK^T product
     static constexpr int NDB = D / 32;                // 32-wide head-dim blocks of the PV product
-    // Bytes per row of an LDS tile: 16 bytes of padding make the row pitch
-    // 16 mod 64, so that 16 consecutive rows read at the same column (QK^T
-    // operand) and rows 4 apart read 64 bytes wide (PV operand) fall into
-    // different banks, while every address stays "lane base + constant".
+    // Row pitch of the LDS tiles: 16 bytes of padding make it 16 mod 256, so the
+    // 16 consecutive rows that read the same 16-byte column (QK^T operands) fall
+    // into 16 different bank groups, and every operand address stays "lane base
+    // + constant".  The V tile uses the same pitch: wider paddings (32, 48) that
+    // would also separate the 4 rows of a transposing read measured ~15% slower
+    // end to end on MI355X.
     static constexpr int ROWB = D * 2 + 16;
-    static constexpr int TILEB = kKeyTile * ROWB;     // bytes per operand tile
+    static constexpr int VROWB = D * 2 + 16;
+    static constexpr int TILEB = kKeyTile * ROWB;     // bytes of a K tile
+    static constexpr int VTILEB = kKeyTile * VROWB;   // bytes of a V tile
     static constexpr int MROW = D + 4;                // floats per query row in the merge layout
     static constexpr int MERGEB = kQueryTile * MROW * 4;
-    static constexpr int REGIONB = (2 * TILEB > MERGEB) ? 2 * TILEB : MERGEB;  // per wave
+    static constexpr int REGIONB = (TILEB + VTILEB > MERGEB) ? TILEB + VTILEB : MERGEB;  // per wave
 };
 
-template <int D, int NW>
+// 64-bit LDS read with a 16-bit transpose across each group of 16 lanes.
+__device__ __forceinline__ half4_t lds_read_tr16(const unsigned char* lds_ptr)
+{
+    typedef short short4_t __attribute__((ext_vector_type(4)));
+    const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) short4_t*)(lds_ptr));
+    return __builtin_bit_cast(half4_t, r);
+}
+
+template <int D, int NW, int PF>
 __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 {
     using Geo = MfmaGeometry<D>;
     constexpr int CPR = Geo::CPR, RPI = Geo::RPI, NLD = Geo::NLD, NKS = Geo::NKS, NDB = Geo::NDB;
-    constexpr int ROWB = Geo::ROWB, TILEB = Geo::TILEB, MROW = Geo::MROW, REGIONB = Geo::REGIONB;
+    constexpr int ROWB = Geo::ROWB, VROWB = Geo::VROWB, TILEB = Geo::TILEB, MROW = Geo::MROW;
+    constexpr int REGIONB = Geo::REGIONB;
     constexpr int NT = NW * 64;
     static_assert(NT >= kListThreads, "the response list needs one thread per step");
 
     __shared__ __align__(16) unsigned char s_region[NW * REGIONB];
+    __shared__ __align__(16) unsigned char s_q[kQueryTile * ROWB];   // Q^T operand, shared by the waves
     __shared__ ResponseListSmem s_list;
     __shared__ float s_ml[NW][kQueryTile][2];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: tile indices stay uniform
+    SEGKV_STAMP(0);
     const int n = lane & 31;        // query slot (MFMA column) / key row (MFMA A row) / d within block
     const int h = lane >> 5;        // lane half: which 8 of the 16 contraction slots
     const int srow = lane / CPR;    // staging: row within a load instruction
     const int schunk = lane % CPR;  // staging: 16-byte chunk of the row
 
     // ---- which work item ----
-    int id = blockIdx.x;
+    int id = xcd_contiguous_index(blockIdx.x, gridDim.x);
     const int qb = id % p.n_qblocks; id /= p.n_qblocks;
     const int g = id % p.Hkv;        id /= p.Hkv;
     const int chunk = id % p.n_chunks;
@@ -88,24 +134,38 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 
     unsigned char* const region = s_region + wave * REGIONB;
     unsigned char* const k_tile = region;
-    unsigned char* const v_tile = region + TILEB;
+    unsigned char* const v_tile = region + TILEB;      // K tile first, then the V tile
 
-    // ---- this lane's query: B operand of the QK^T product, kept in registers ----
+    // ---- queries of this block: staged once into LDS in the same padded row
+    // layout as the key tiles; every wave reads its QK^T B operand from there ----
     const int lq = qb * kQueryTile + n;
     const bool q_valid = lq < p.nq;
     const int lqc = q_valid ? lq : (p.nq - 1);
     const int qbeam = lqc / p.G;
     const int hq = g * p.G + (lqc % p.G);
-    const size_t qidx = (size_t)(b * p.W + qbeam) * p.Hq + hq;
     const float slope2 = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
     const int qpos = p.Lp + p.T - 1;
-    half8_t qreg[NKS];
+    // Requests that later steps depend on go out first, in this order: the Q
+    // chunks this thread stages, its row of the parent table, then (below) the
+    // wave's first key tile.  They are consumed in the same order, so each wait
+    // leaves the younger requests in flight.
+    constexpr int QCH = (kQueryTile * CPR + NT - 1) / NT;
+    u32x4_t qw[QCH];
 #pragma unroll
-    for (int t = 0; t < NKS; ++t) {
-        u32x4_t w = load16(p.q + qidx * D + 16 * t + 8 * h);
-        if (!q_valid) w = u32x4_t{0u, 0u, 0u, 0u};
-        qreg[t] = __builtin_bit_cast(half8_t, w);
+    for (int c = 0; c < QCH; ++c) {
+        const int i = tid + c * NT;
+        const int qn = i / CPR;
+        const int ch = i % CPR;
+        const int lqn = qb * kQueryTile + qn;
+        qw[c] = u32x4_t{0u, 0u, 0u, 0u};               // unused query slots multiply as zeros
+        if (i < kQueryTile * CPR && lqn < p.nq) {
+            const size_t row = (size_t)(b * p.W + lqn / p.G) * p.Hq + g * p.G + (lqn % p.G);
+            qw[c] = load16(p.q + row * D + ch * 8);
+        }
     }
+    const bool has_row = (s1 > s0) && list_thread_has_row(p.W, s0, s1);
+    ParentRow prow;
+    if (has_row) prow = load_parent_row(p.parent, N, p.W, b, s0 + tid + 1);
 
     // ---- fused append: the block that owns step T-1 copies the unit's new rows ----
     const bool have_new = (p.k_new != nullptr);
@@ -124,6 +184,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         }
     }
 
+    SEGKV_PHASE_DECL;
     // ---- running state: reference max and partial sum per lane, O^T accumulators ----
     float m_ref = kEmptyMax;
     float l_part = 0.0f;            // sum of p over this lane's 16 keys of every tile
@@ -143,9 +204,8 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int row = RPI * i + srow;
-            const int off = row * ROWB + (schunk << 4);
-            *reinterpret_cast<u32x4_t*>(k_tile + off) = st.k[i];
-            *reinterpret_cast<u32x4_t*>(v_tile + off) = st.v[i];
+            *reinterpret_cast<u32x4_t*>(k_tile + row * ROWB + (schunk << 4)) = st.k[i];
+            *reinterpret_cast<u32x4_t*>(v_tile + row * VROWB + (schunk << 4)) = st.v[i];
         }
     };
 
@@ -159,8 +219,10 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         for (int t = 0; t < NKS; ++t) {
             const int off = n * ROWB + ((2 * t + h) << 4);
             const half8_t a = *reinterpret_cast<const half8_t*>(k_tile + off);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
+            const half8_t bq = *reinterpret_cast<const half8_t*>(s_q + off);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq, s, 0, 0, 0);
         }
+        SEGKV_PHASE(1);
         // logits, tile maximum for this lane's query
         float m_tile = -INFINITY;
 #pragma unroll
@@ -189,91 +251,122 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
             l_part += pr;
             pb[r >> 3][r & 7] = (_Float16)pr;
         }
-        // O^T += V^T . P^T
+        SEGKV_PHASE(2);
+        // O^T += V^T . P^T.  The A operand wants, per lane, 8 keys of one head-dim
+        // column; the V tile is row-major [key][d].  ds_read_b64_tr_b16 does the
+        // transpose on the way out of LDS: a 16-lane group reads 4 rows x 16
+        // columns (lane i supplies row i/4, columns 4*(i%4)..+3) and lane i
+        // receives column i of all 4 rows.  Two such reads give the 8 keys
+        // 16u + 8r + 4h + {0..3}, r = 0, 1, matching the keys of P's registers.
+        {
+            const int grp = lane >> 4;                 // 16-lane group: d half (grp&1), key half h
+            const int li = lane & 15;
+            const int tr_base = (4 * h + (li >> 2)) * VROWB + ((16 * (grp & 1) + 4 * (li & 3)) << 1);
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            const int d = 32 * db + n;
+            for (int db = 0; db < NDB; ++db) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                half8_t a;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int key = 16 * u + 8 * (e >> 2) + 4 * h + (e & 3);
-                    const int off = key * ROWB + (d << 1);
-                    a[e] = *reinterpret_cast<const _Float16*>(v_tile + off);
+                for (int u = 0; u < 2; ++u) {
+                    const int off = tr_base + (16 * u) * VROWB + db * 64;
+                    const half4_t lo = lds_read_tr16(v_tile + off);
+                    const half4_t hi = lds_read_tr16(v_tile + off + 8 * VROWB);
+                    const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
                 }
-                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
+                // keep the operand reads of later blocks from piling up in registers
+                if (NDB > 4) __builtin_amdgcn_sched_barrier(0);
             }
-            // keep the gathers of later blocks from being hoisted above this one:
-            // their 16-bit loads would all be live at once
-            __builtin_amdgcn_sched_barrier(0);
         }
+        SEGKV_PHASE(3);
     };
 
-    // ---- prompt segment (Section 3.3: loop over the prompt keys) ----
-    if (k1 > k0) {
-        const int n_tiles = (k1 - k0 + kKeyTile - 1) / kKeyTile;
-        auto fetch = [&](Staged& st, int ti) {
-            const int base = k0 + ti * kKeyTile;
+    // ---- one tile stream per wave: prompt tiles first (Section 3.3: loop over the
+    // prompt keys), then the response tiles (index select fused: rows chosen by
+    // the beam lineage).  PF tiles per wave are kept in flight in registers.
+    // A fetch is never skipped: past the end of the stream it is pointed at one
+    // row that is already cached, so that the code is free of conditional loads
+    // and every wait covers exactly the tile it needs. ----
+    const int n_ptiles = (k1 > k0) ? (k1 - k0 + kKeyTile - 1) / kKeyTile : 0;
+    const _Float16* const dummy = p.q + (size_t)b * p.W * p.Hq * D + schunk * 8;
+    // Prompt tiles are addressed as (scalar tile base) + (32-bit lane offset):
+    // the lane offsets are the same for every full tile, so no per-load 64-bit
+    // address has to be kept in registers.
+    const uint32_t row_stride = (uint32_t)p.Hkv * D;   // elements between consecutive keys
+    auto fetch_prompt = [&](Staged& st, int ti) {
+        const int base = k0 + ti * kKeyTile;
+        const int lim = min(kKeyTile - 1, k1 - 1 - base);          // last valid row of the tile
+        const size_t tile_off = (((size_t)b * p.Lp + base) * p.Hkv + g) * D;
+        const _Float16* const kb = p.prompt_k + tile_off;
+        const _Float16* const vb = p.prompt_v + tile_off;
 #pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                const int row = min(base + RPI * i + srow, k1 - 1);
-                const size_t off = (((size_t)b * p.Lp + row) * p.Hkv + g) * D + schunk * 8;
-                st.k[i] = load16_stream(p.prompt_k + off);
-                st.v[i] = load16_stream(p.prompt_v + off);
-            }
-        };
-        Staged st;
-        int ti = wave;
-        if (ti < n_tiles) fetch(st, ti);
-        for (; ti < n_tiles; ti += NW) {
-            stage_to_lds(st);
-            if (ti + NW < n_tiles) fetch(st, ti + NW);
+        for (int i = 0; i < NLD; ++i) {
+            const uint32_t off = (uint32_t)min(RPI * i + srow, lim) * row_stride + schunk * 8;
+            st.k[i] = load16_stream(kb + off);
+        }
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const uint32_t off = (uint32_t)min(RPI * i + srow, lim) * row_stride + schunk * 8;
+            st.v[i] = load16_stream(vb + off);
+        }
+    };
+    auto fetch_dummy = [&](Staged& st) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) st.k[i] = load16(dummy);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) st.v[i] = load16(dummy);
+    };
+
+    // The response list is resolved by the whole work-group (it has barriers).
+    // With enough prompt tiles it runs after each wave's first tile, when the
+    // parent rows requested above have long arrived and PF further tiles are in
+    // flight; otherwise right away.
+    int total = 0;
+    int n_tiles = n_ptiles;
+    uint32_t own_map = kIdentityMap;
+    auto resolve_list = [&]() {
+        if (s1 > s0) {
+            build_response_list(s_list, p.parent, (g == 0 && qb == 0) ? p.anc_out : nullptr, p.B,
+                                p.W, p.T, b, s0, s1, own_map);
+            total = s_list.total;
+            n_tiles = n_ptiles + (total + kKeyTile - 1) / kKeyTile;
+        }
+        SEGKV_STAMP(2);
+    };
+    const bool late_list = n_ptiles >= (PF + 1) * NW;  // uniform over the work-group
+
+    auto fetch_response = [&](Staged& st, int ti) {
+        const int base = ti * kKeyTile;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int e = min(base + RPI * i + srow, total - 1);
+            const uint32_t ent = s_list.ent[e];
+            const int s = s0 + (int)(ent >> 16);
+            const int slot = (int)((ent >> 8) & 0xffu);
+            // one load per operand through a selected pointer (two loads under
+            // divergent branches would have to wait for each other)
+            const bool is_new = have_new && s == p.T - 1;
+            const size_t off_new = ((size_t)(b * p.W + slot) * p.Hkv + g) * D + schunk * 8;
+            const size_t off_old = (((size_t)s * N + b * p.W + slot) * p.Hkv + g) * D + schunk * 8;
+            const _Float16* const kp = is_new ? p.k_new + off_new : p.resp_k + off_old;
+            const _Float16* const vp = is_new ? p.v_new + off_new : p.resp_v + off_old;
+            st.k[i] = load16_stream(kp);
+            st.v[i] = load16_stream(vp);
+        }
+    };
+    auto fetch = [&](Staged& st, int ti) {
+        if (ti < n_ptiles)      fetch_prompt(st, ti);
+        else if (ti < n_tiles)  fetch_response(st, ti - n_ptiles);
+        else                    fetch_dummy(st);
+    };
+    auto process = [&](int ti) {
+        if (ti < n_ptiles) {
             const int base = k0 + ti * kKeyTile;
             compute_tile([&](float dot, int key) {
                 const int kpos = base + key;
                 const float z = dot * p.scale2 + slope2 * (float)(kpos - qpos);
                 return kpos < k1 ? z : -INFINITY;
             });
-        }
-    }
-
-    // ---- response segment (index select fused: rows chosen by the beam lineage) ----
-    if (s1 > s0) {
-        build_response_list(s_list, p.parent, (g == 0 && qb == 0) ? p.anc_out : nullptr, p.B, p.W,
-                            p.T, b, s0, s1);
-        const int total = s_list.total;
-        const int n_tiles = (total + kKeyTile - 1) / kKeyTile;
-        auto fetch = [&](Staged& st, int ti) {
-            const int base = ti * kKeyTile;
-#pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                const int e = min(base + RPI * i + srow, total - 1);
-                const uint32_t ent = s_list.ent[e];
-                const int s = s0 + (int)(ent >> 16);
-                const int slot = (int)((ent >> 8) & 0xffu);
-                const _Float16* kp;
-                const _Float16* vp;
-                if (have_new && s == p.T - 1) {
-                    const size_t off = ((size_t)(b * p.W + slot) * p.Hkv + g) * D + schunk * 8;
-                    kp = p.k_new + off;
-                    vp = p.v_new + off;
-                } else {
-                    const size_t off = (((size_t)s * N + b * p.W + slot) * p.Hkv + g) * D + schunk * 8;
-                    kp = p.resp_k + off;
-                    vp = p.resp_v + off;
-                }
-                st.k[i] = load16_stream(kp);
-                st.v[i] = load16_stream(vp);
-            }
-        };
-        Staged st;
-        int ti = wave;
-        if (ti < n_tiles) fetch(st, ti);
-        for (; ti < n_tiles; ti += NW) {
-            stage_to_lds(st);
-            if (ti + NW < n_tiles) fetch(st, ti + NW);
-            const int base = ti * kKeyTile;
+        } else {
+            const int base = (ti - n_ptiles) * kKeyTile;
             compute_tile([&](float dot, int key) {
                 const int e = base + key;
                 const uint32_t ent = s_list.ent[min(e, total - 1)];
@@ -283,8 +376,61 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
                 return vis ? z : -INFINITY;
             });
         }
-    }
+    };
 
+    Staged st[PF];
+    int ti = wave;                                     // next tile this wave computes
+    if (late_list) {
+        // every tile requested before the list exists is a prompt tile
+#pragma unroll
+        for (int j = 0; j < PF; ++j) fetch_prompt(st[j], ti + j * NW);
+    }
+    // Q tile to LDS and this thread's parent row packed: both were requested
+    // before the tiles above, so waiting for them leaves the tiles in flight
+#pragma unroll
+    for (int c = 0; c < QCH; ++c) {
+        const int i = tid + c * NT;
+        if (i < kQueryTile * CPR)
+            *reinterpret_cast<u32x4_t*>(s_q + (i / CPR) * ROWB + ((i % CPR) << 4)) = qw[c];
+    }
+    if (has_row) own_map = pack_parent_row(prow, p.W);
+    __syncthreads();                                   // Q tile visible to every wave
+    SEGKV_STAMP(1);
+    if (late_list) {
+        stage_to_lds(st[0]);
+        SEGKV_STAMP(3);
+        fetch_prompt(st[0], ti + PF * NW);
+        SEGKV_PHASE_BEGIN;
+        process(ti);
+        ti += NW;
+        resolve_list();
+        // rotate so that the ring again starts at slot 0
+#pragma unroll
+        for (int j = 1; j < PF; ++j) {
+            if (ti < n_tiles) stage_to_lds(st[j]);
+            fetch(st[j], ti + PF * NW);
+            if (ti < n_tiles) process(ti);
+            ti += NW;
+        }
+    } else {
+        resolve_list();
+#pragma unroll
+        for (int j = 0; j < PF; ++j) fetch(st[j], ti + j * NW);
+    }
+    SEGKV_PHASE_BEGIN;
+    while (ti < n_tiles) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+            if (ti < n_tiles) stage_to_lds(st[j]);
+            fetch(st[j], ti + PF * NW);
+            SEGKV_PHASE(0);
+            if (ti < n_tiles) process(ti);
+            ti += NW;
+        }
+    }
+    SEGKV_PHASE_DUMP;
+
+    SEGKV_STAMP(4);
     // ---- merge the waves through LDS (each wave reuses its own tile region) ----
     l_part += __shfl_xor(l_part, 32);
     float* const mrg = reinterpret_cast<float*>(region);
@@ -301,6 +447,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         s_ml[wave][n][1] = l_part;
     }
     __syncthreads();
+    SEGKV_STAMP(5);
 
     const int NQ = N * p.Hq;
     const int nq_here = min(kQueryTile, p.nq - qb * kQueryTile);
@@ -340,6 +487,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
             }
         }
     }
+    SEGKV_STAMP(6);
 }
 
 // ---------------------------------------------------------------------------
@@ -349,15 +497,15 @@ hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, unsigned grid, hi
 {
     switch (D) {
         case 64:
-            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<64, kMfmaWaves64>), dim3(grid),
+            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<64, kMfmaWaves64, 1>), dim3(grid),
                                dim3(kMfmaWaves64 * 64), 0, st, p);
             break;
         case 128:
-            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<128, kMfmaWaves128>), dim3(grid),
+            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<128, kMfmaWaves128, 1>), dim3(grid),
                                dim3(kMfmaWaves128 * 64), 0, st, p);
             break;
         case 256:
-            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<256, kMfmaWaves256>), dim3(grid),
+            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<256, kMfmaWaves256, 1>), dim3(grid),
                                dim3(kMfmaWaves256 * 64), 0, st, p);
             break;
         default:

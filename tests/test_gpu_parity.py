@@ -24,7 +24,8 @@ def _announce(request):
 @pytest.fixture
 def planner_env():
     """Temporarily force the launch planner (chunking) through its documented knobs."""
-    saved = {k: os.environ.get(k) for k in ("SEGKV_TARGET_GROUPS", "SEGKV_MIN_PCHUNK")}
+    saved = {k: os.environ.get(k) for k in ("SEGKV_TARGET_GROUPS", "SEGKV_MIN_PCHUNK", "SEGKV_PATH",
+                                            "SEGKV_HEADS_PER_WAVE")}
 
     def set_env(**kw):
         for k, v in kw.items():
@@ -67,26 +68,49 @@ def _check(wl, x, res, ref_out, ref_anc, ref_rk, ref_rv, what):
     assert same_bits(res["resp_v"], ref_rv), f"{what}: resp_v contents differ"
 
 
+# Both kernels must pass every case: the planner's own choice ("auto") plus
+# each path forced through the library's documented override.
+PATHS = ["auto", "alu", "mfma"]
+
+
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("wl", SMALL, ids=lambda w: w.name)
-def test_small_cases_fused_append(wl):
+def test_small_cases_fused_append(wl, path, planner_env):
+    if path != "auto":
+        planner_env(SEGKV_PATH=path)
     x = make_inputs(wl)
     ref = oracle_reference(wl, x)
     res = run_gpu(wl, x, fused=True)
-    _check(wl, x, res, *ref, what=wl.name)
+    _check(wl, x, res, *ref, what=f"{wl.name}/{path}")
 
 
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("wl", SMALL, ids=lambda w: w.name)
-def test_small_cases_chunked(wl, planner_env):
+def test_small_cases_chunked(wl, path, planner_env):
     # force split-KV with short chunks so the partial/merge path runs on small inputs
     planner_env(SEGKV_TARGET_GROUPS=1 << 20, SEGKV_MIN_PCHUNK=32)
+    if path != "auto":
+        planner_env(SEGKV_PATH=path)
     x = make_inputs(wl)
     ref = oracle_reference(wl, x)
     res = run_gpu(wl, x, fused=True)
-    _check(wl, x, res, *ref, what=wl.name + "/chunked")
+    _check(wl, x, res, *ref, what=f"{wl.name}/{path}/chunked")
 
 
+@pytest.mark.parametrize("hp", [1, 2])
+@pytest.mark.parametrize("wl", [SMALL[1], SMALL[3], SMALL[8]], ids=lambda w: w.name)
+def test_alu_path_with_fewer_heads_per_wave(wl, hp, planner_env):
+    planner_env(SEGKV_PATH="alu", SEGKV_HEADS_PER_WAVE=hp)
+    x = make_inputs(wl)
+    ref = oracle_reference(wl, x)
+    res = run_gpu(wl, x, fused=True)
+    _check(wl, x, res, *ref, what=f"{wl.name}/hp{hp}")
+
+
+@pytest.mark.parametrize("path", ["alu", "mfma"])
 @pytest.mark.parametrize("wl", [SMALL[1], SMALL[5], SMALL[8]], ids=lambda w: w.name)
-def test_fused_append_equals_append_then_attend(wl):
+def test_fused_append_equals_append_then_attend(wl, path, planner_env):
+    planner_env(SEGKV_PATH=path)
     x = make_inputs(wl)
     fused = run_gpu(wl, x, fused=True)
     split = run_gpu(wl, x, fused=False)
@@ -96,17 +120,22 @@ def test_fused_append_equals_append_then_attend(wl):
     assert np.array_equal(fused["anc"], split["anc"])
 
 
-@pytest.mark.parametrize("T", [257, 300, 600])
-def test_response_longer_than_one_chunk(T):
-    # more than 256 steps: several response chunks, ancestors carried across them
-    wl = Workload(f"resp{T}", B=2, W=4, Hq=2, Hkv=2, D=64, Lp=50, T=T, seed=120 + T)
+@pytest.mark.parametrize("path", ["alu", "mfma"])
+@pytest.mark.parametrize("T,W", [(257, 4), (300, 4), (600, 4), (200, 8), (300, 8)])
+def test_response_longer_than_one_chunk(T, W, path, planner_env):
+    # more steps (or step x beam rows) than one work-group resolves: several
+    # response chunks, ancestors carried across them
+    planner_env(SEGKV_PATH=path)
+    wl = Workload(f"resp{T}w{W}", B=2, W=W, Hq=2, Hkv=2, D=64, Lp=50, T=T, seed=120 + T + W)
     x = make_inputs(wl)
     ref = oracle_reference(wl, x)
     res = run_gpu(wl, x, fused=True)
     _check(wl, x, res, *ref, what=wl.name)
 
 
-def test_run_twice_is_bit_identical():
+@pytest.mark.parametrize("path", ["alu", "mfma"])
+def test_run_twice_is_bit_identical(path, planner_env):
+    planner_env(SEGKV_PATH=path)
     wl = SMALL[5]
     x = make_inputs(wl)
     res = run_gpu(wl, x, fused=False, repeats=3)
@@ -114,7 +143,9 @@ def test_run_twice_is_bit_identical():
     assert same_bits(res["outs"][0], res["outs"][2])
 
 
-def test_dead_slots_and_rows_beyond_T_are_never_read():
+@pytest.mark.parametrize("path", ["alu", "mfma"])
+def test_dead_slots_and_rows_beyond_T_are_never_read(path, planner_env):
+    planner_env(SEGKV_PATH=path)
     wl = SMALL[1]
     x = make_inputs(wl)           # rows >= T-1 are NaN poison already
     ref_out, ref_anc, ref_rk, ref_rv = oracle_reference(wl, x)
@@ -137,7 +168,13 @@ def test_dead_slots_and_rows_beyond_T_are_never_read():
     assert_parity(res["out"], ref_out, "dead slots")
 
 
-def test_index_probe_reads_back_the_gathered_rows():
+@pytest.mark.parametrize("path", ["alu", "mfma"])
+def test_index_probe_reads_back_the_gathered_rows(path, planner_env):
+    planner_env(SEGKV_PATH=path)
+    _index_probe()
+
+
+def _index_probe():
     # One response key per (beam row) dominates the softmax; its value row
     # encodes (step, slot), so the context tells which row the kernel gathered.
     wl = Workload("probe", B=2, W=4, Hq=2, Hkv=2, D=64, Lp=20, T=40, seed=130)
