@@ -27,6 +27,16 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 MALL_BYTES = 256 << 20
 
+# HBM bytes per launch of the decode kernel, measured with rocprofv3
+# (FETCH_SIZE + WRITE_SIZE, each scaled by a copy kernel of known size); the
+# figures and the commands behind them are in profiles/sdpa_decode_*.md.
+MEASURED_TRAFFIC_BYTES = {
+    "llama2_7b_greedy": 2420205095,
+    "llama2_70b_gqa": 308337971,
+    "gptj6b": 316132774,
+    "bloom176b_alibi": 545889316,
+}
+
 
 def algorithmic_bytes(wl, unique_rows: int) -> dict:
     """Bytes one layer-step must move: prompt K/V once per request, the distinct
@@ -164,7 +174,7 @@ def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_second
         "bound": "hbm", "achieved": nbytes["unique"] / (dev_ms.mean() * 1e-3) / 1e9,
         "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": nbytes["unique"] / (dev_ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
     }
 
     if want_cpu_baseline:
@@ -175,14 +185,16 @@ def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_second
 
 
 def cpu_baseline(wl, x, bytes_unique, budget_s, U):
-    """The fp64 oracle as it stands, timed on this machine's host cores on the first
-    requests of the same batch (a bounded sample), scaled to the metric's unit."""
+    """The fp64 oracle as it stands, timed on this machine's host cores on a bounded
+    sample of the same batch: the first requests (all of them if they fit the
+    budget), repeated until about `budget_s` CPU-core-seconds have been spent."""
     import numpy as np
     from oracle import segkv_oracle as oracle
 
     rk, rv = x["resp_k"], x["resp_v"]
     oracle.append_kv(rk, rv, x["k_new"], x["v_new"], wl.T - 1)
     per_req = wl.W * wl.Hq
+    cores = oracle.num_threads()
 
     def run(nreq):
         pairs = np.array([(n, h) for n in range(nreq * wl.W) for h in range(wl.Hq)], dtype=np.int32)
@@ -192,14 +204,51 @@ def cpu_baseline(wl, x, bytes_unique, budget_s, U):
         return time.perf_counter() - t0
 
     t1 = run(1)                                   # calibrate on one request
-    nreq = int(max(1, min(wl.B, budget_s / max(t1, 1e-4))))
-    t = run(nreq)
+    wall_budget = budget_s / max(cores, 1)
+    nreq = int(max(1, min(wl.B, wall_budget / max(t1, 1e-5))))
+    times = [run(nreq)]
+    while sum(times) < wall_budget and len(times) < 50:
+        times.append(run(nreq))
+    t = float(np.median(times))
     frac = nreq / wl.B
-    return {"value": bytes_unique * frac / t / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+    return {"value": bytes_unique * frac / t / 1e9, "unit": "GB/s", "cores": cores,
             "kind": "oracle",
             "sample": f"first {nreq} of {wl.B} requests ({nreq * per_req} of {wl.B * per_req} "
-                      f"query rows), {t:.2f} s wall",
+                      f"query rows), {len(times)} repeats, median {t:.3f} s wall each, "
+                      f"{sum(times) * cores:.0f} core-seconds in total",
             "ms_per_step_extrapolated": t / frac * 1e3}
+
+
+def run_counter_calibration(segkv, torch):
+    """Kernels of known HBM traffic for scaling hardware counters: a copy
+    (append of one very wide row: 2 x 128 MiB read, 2 x 128 MiB written) and a
+    pure read of 1 GiB.  Each runs three times on cold buffers."""
+    dev = torch.device("cuda:0")
+    n_rows, hkv, d = 1 << 15, 16, 128                      # 32768*16*128*2 B = 128 MiB per tensor
+    dims = segkv.make_dims(n_rows, 1, hkv, hkv, d, 0, 1, 1)
+    row = n_rows * hkv * d
+    for _ in range(3):
+        src_k = torch.ones(row, dtype=torch.float16, device=dev)
+        src_v = torch.ones(row, dtype=torch.float16, device=dev)
+        dst_k = torch.empty(row, dtype=torch.float16, device=dev)
+        dst_v = torch.empty(row, dtype=torch.float16, device=dev)
+        flush = torch.zeros(1 << 28, dtype=torch.float16, device=dev)   # 512 MiB: evicts the caches
+        flush.add_(1)
+        torch.cuda.synchronize()
+        segkv.append_kv(dst_k, dst_v, src_k, src_v, 0, dims)
+        torch.cuda.synchronize()
+        del src_k, src_v, dst_k, dst_v, flush
+    sink = torch.empty(4096, dtype=torch.int32, device=dev)
+    for _ in range(3):
+        buf = torch.ones(1 << 29, dtype=torch.float16, device=dev)      # 1 GiB
+        flush = torch.zeros(1 << 28, dtype=torch.float16, device=dev)
+        flush.add_(1)
+        torch.cuda.synchronize()
+        segkv.stream_read_probe(buf, sink)
+        torch.cuda.synchronize()
+        del buf, flush
+    return {"append_kv_kernel": {"bytes_read": 2 * row * 2, "bytes_written": 2 * row * 2},
+            "stream_read_probe_kernel": {"bytes_read": 1 << 30, "bytes_written": 4096 * 4}}
 
 
 def main():
@@ -210,8 +259,13 @@ def main():
     ap.add_argument("--workload", default="llama2_7b_greedy")
     ap.add_argument("--others", default="llama2_70b_gqa,gptj6b,bloom176b_alibi",
                     help="comma list of further workloads reported under other_workloads ('' = none)")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--cpu-seconds", type=float, default=20.0,
+                    help="CPU-core-seconds to spend on the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-counters", action="store_true",
+                    help="also launch a plain copy of known size (segkv_append_kv, 2 x 128 MiB read and "
+                         "written) and a plain read of known size (segkv_stream_read_probe, 1 GiB), "
+                         "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -233,6 +287,10 @@ def main():
     for name in [n for n in a.others.split(",") if n and n != a.workload]:
         others.append(time_workload(CONFIGS[name], a.steps, a.warmup, segkv, torch, False, 0))
 
+    calibration = None
+    if a.calibrate_counters:
+        calibration = run_counter_calibration(segkv, torch)
+
     line = {
         "metric": "fused segment-KV decode SDPA: achieved HBM GB/s (us/layer-step in us_per_layer_step)",
         "value": main_res["gbs_unique"], "unit": "GB/s",
@@ -248,6 +306,7 @@ def main():
         "detail": {k: main_res[k] for k in ("bytes_unique", "bytes_nominal", "unique_response_rows",
                                             "gbs_nominal", "device_us", "stream_read_probe_gbs",
                                             "workspace_bytes")},
+        "counter_calibration": calibration,
         "other_workloads": [{k: r[k] for k in ("workload", "shape", "us_per_layer_step", "gbs_unique",
                                                "gbs_nominal", "bytes_unique", "device_us", "roofline",
                                                "stream_read_probe_gbs", "buffer_sets")}
