@@ -45,6 +45,10 @@ def load_library():
         return _lib
     if not _build.is_built():
         _build.build_library()
+    # PyTorch owns the device memory and streams that are handed to the library,
+    # so both must talk to the same HIP runtime: import torch first, so that the
+    # runtime it ships is the one libsegkv.so resolves its HIP symbols against.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_build.LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     dp = ctypes.POINTER(SegkvDims)
