@@ -87,7 +87,7 @@ __device__ __forceinline__ half4_t lds_read_tr16(const unsigned char* lds_ptr)
     return __builtin_bit_cast(half4_t, r);
 }
 
-template <int D, int NW, int PF>
+template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 {
     using Geo = MfmaGeometry<D>;
@@ -101,6 +101,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     __shared__ __align__(16) unsigned char s_q[kQueryTile * ROWB];   // Q^T operand, shared by the waves
     __shared__ ResponseListSmem s_list;
     __shared__ float s_ml[NW][kQueryTile][2];
+    __shared__ int s_next_tile;                        // next unclaimed tile of the stream
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -200,7 +201,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     };
 
     // registers -> the wave's LDS tiles
-    auto stage_to_lds = [&](const Staged& st) {
+    auto stage_to_lds = [&](const Staged& st) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int row = RPI * i + srow;
@@ -209,8 +210,10 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         }
     };
 
-    // One tile of 32 keys: z_of(r, key) gives the masked base-2 logit for S^T register r.
-    auto compute_tile = [&](auto&& logit_of) {
+    // One tile of 32 keys.  `mode` (uniform) selects how S^T becomes base-2 logits:
+    // 0 full prompt tile without positional bias, 1 prompt tile with masking of
+    // the tail and ALiBi, 2 response tile (per-row beam masks and positions).
+    auto compute_tile = [&](int mode, int base, int total) __attribute__((always_inline)) {
         // S^T = K . Q^T
         float16_t s;
 #pragma unroll
@@ -225,11 +228,31 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         SEGKV_PHASE(1);
         // logits, tile maximum for this lane's query
         float m_tile = -INFINITY;
+        if (mode == 0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = 8 * (r >> 2) + 4 * h + (r & 3);
-            s[r] = logit_of(s[r], key);
-            m_tile = fmaxf(m_tile, s[r]);
+            for (int r = 0; r < 16; ++r) {
+                s[r] *= p.scale2;
+                m_tile = fmaxf(m_tile, s[r]);
+            }
+        } else if (mode == 1) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kpos = base + 8 * (r >> 2) + 4 * h + (r & 3);
+                const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
+                s[r] = kpos < k1 ? z : -INFINITY;
+                m_tile = fmaxf(m_tile, s[r]);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int e = base + 8 * (r >> 2) + 4 * h + (r & 3);
+                const uint32_t ent = s_list.ent[min(e, total - 1)];
+                const int kpos = p.Lp + s0 + (int)(ent >> 16);
+                const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
+                const bool vis = (e < total) && ((ent >> qbeam) & 1u);
+                s[r] = vis ? z : -INFINITY;
+                m_tile = fmaxf(m_tile, s[r]);
+            }
         }
         m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
         // move the reference maximum only when a tile exceeds it by the slack
@@ -279,19 +302,21 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         SEGKV_PHASE(3);
     };
 
-    // ---- one tile stream per wave: prompt tiles first (Section 3.3: loop over the
-    // prompt keys), then the response tiles (index select fused: rows chosen by
-    // the beam lineage).  PF tiles per wave are kept in flight in registers.
-    // A fetch is never skipped: past the end of the stream it is pointed at one
-    // row that is already cached, so that the code is free of conditional loads
-    // and every wait covers exactly the tile it needs. ----
+    // ---- one tile stream per work-group: prompt tiles first (Section 3.3: loop
+    // over the prompt keys), then the response tiles (index select fused: rows
+    // chosen by the beam lineage).  Waves claim tiles from a shared counter, so a
+    // wave whose loads come back sooner takes more of them.  Each wave keeps one
+    // tile in flight in registers while it computes the previous one.  A fetch is
+    // never skipped: past the end of the stream it is pointed at one row that is
+    // already cached, so that the code is free of conditional loads and every
+    // wait covers exactly the tile it needs. ----
     const int n_ptiles = (k1 > k0) ? (k1 - k0 + kKeyTile - 1) / kKeyTile : 0;
     const _Float16* const dummy = p.q + (size_t)b * p.W * p.Hq * D + schunk * 8;
     // Prompt tiles are addressed as (scalar tile base) + (32-bit lane offset):
     // the lane offsets are the same for every full tile, so no per-load 64-bit
     // address has to be kept in registers.
     const uint32_t row_stride = (uint32_t)p.Hkv * D;   // elements between consecutive keys
-    auto fetch_prompt = [&](Staged& st, int ti) {
+    auto fetch_prompt = [&](Staged& st, int ti) __attribute__((always_inline)) {
         const int base = k0 + ti * kKeyTile;
         const int lim = min(kKeyTile - 1, k1 - 1 - base);          // last valid row of the tile
         const size_t tile_off = (((size_t)b * p.Lp + base) * p.Hkv + g) * D;
@@ -308,7 +333,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
             st.v[i] = load16_stream(vb + off);
         }
     };
-    auto fetch_dummy = [&](Staged& st) {
+    auto fetch_dummy = [&](Staged& st) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) st.k[i] = load16(dummy);
 #pragma unroll
@@ -317,7 +342,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 
     // The response list is resolved by the whole work-group (it has barriers).
     // With enough prompt tiles it runs after each wave's first tile, when the
-    // parent rows requested above have long arrived and PF further tiles are in
+    // parent rows requested above have long arrived and the next tile is in
     // flight; otherwise right away.
     int total = 0;
     int n_tiles = n_ptiles;
@@ -331,9 +356,14 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         }
         SEGKV_STAMP(2);
     };
-    const bool late_list = n_ptiles >= (PF + 1) * NW;  // uniform over the work-group
+    const bool late_list = n_ptiles >= 2 * NW;         // uniform over the work-group
+    auto claim_tile = [&]() {
+        int v = 0;
+        if (lane == 0) v = atomicAdd(&s_next_tile, 1);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
 
-    auto fetch_response = [&](Staged& st, int ti) {
+    auto fetch_response = [&](Staged& st, int ti) __attribute__((always_inline)) {
         const int base = ti * kKeyTile;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
@@ -352,41 +382,28 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
             st.v[i] = load16_stream(vp);
         }
     };
-    auto fetch = [&](Staged& st, int ti) {
+    auto fetch = [&](Staged& st, int ti) __attribute__((always_inline)) {
         if (ti < n_ptiles)      fetch_prompt(st, ti);
         else if (ti < n_tiles)  fetch_response(st, ti - n_ptiles);
         else                    fetch_dummy(st);
     };
-    auto process = [&](int ti) {
+    auto process = [&](int ti) __attribute__((always_inline)) {
         if (ti < n_ptiles) {
             const int base = k0 + ti * kKeyTile;
-            compute_tile([&](float dot, int key) {
-                const int kpos = base + key;
-                const float z = dot * p.scale2 + slope2 * (float)(kpos - qpos);
-                return kpos < k1 ? z : -INFINITY;
-            });
+            const bool plain = (p.slopes == nullptr) && (base + kKeyTile <= k1);
+            compute_tile(plain ? 0 : 1, base, 0);
         } else {
-            const int base = (ti - n_ptiles) * kKeyTile;
-            compute_tile([&](float dot, int key) {
-                const int e = base + key;
-                const uint32_t ent = s_list.ent[min(e, total - 1)];
-                const int kpos = p.Lp + s0 + (int)(ent >> 16);
-                const float z = dot * p.scale2 + slope2 * (float)(kpos - qpos);
-                const bool vis = (e < total) && ((ent >> qbeam) & 1u);
-                return vis ? z : -INFINITY;
-            });
+            compute_tile(2, (ti - n_ptiles) * kKeyTile, total);
         }
     };
 
-    Staged st[PF];
-    int ti = wave;                                     // next tile this wave computes
-    if (late_list) {
-        // every tile requested before the list exists is a prompt tile
-#pragma unroll
-        for (int j = 0; j < PF; ++j) fetch_prompt(st[j], ti + j * NW);
-    }
+    Staged st;
+    int ti = wave;                                     // first tile of every wave is its own index
+    if (tid == 0) s_next_tile = NW;
+    // every tile requested before the list exists is a prompt tile
+    if (late_list) fetch_prompt(st, ti);
     // Q tile to LDS and this thread's parent row packed: both were requested
-    // before the tiles above, so waiting for them leaves the tiles in flight
+    // before the tile above, so waiting for them leaves the tile in flight
 #pragma unroll
     for (int c = 0; c < QCH; ++c) {
         const int i = tid + c * NT;
@@ -394,38 +411,24 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
             *reinterpret_cast<u32x4_t*>(s_q + (i / CPR) * ROWB + ((i % CPR) << 4)) = qw[c];
     }
     if (has_row) own_map = pack_parent_row(prow, p.W);
-    __syncthreads();                                   // Q tile visible to every wave
+    __syncthreads();                                   // Q tile and tile counter visible
     SEGKV_STAMP(1);
-    if (late_list) {
-        stage_to_lds(st[0]);
-        SEGKV_STAMP(3);
-        fetch_prompt(st[0], ti + PF * NW);
-        SEGKV_PHASE_BEGIN;
-        process(ti);
-        ti += NW;
+    bool list_pending = late_list;                     // uniform over the work-group
+    if (!late_list) {
         resolve_list();
-        // rotate so that the ring again starts at slot 0
-#pragma unroll
-        for (int j = 1; j < PF; ++j) {
-            if (ti < n_tiles) stage_to_lds(st[j]);
-            fetch(st[j], ti + PF * NW);
-            if (ti < n_tiles) process(ti);
-            ti += NW;
-        }
-    } else {
-        resolve_list();
-#pragma unroll
-        for (int j = 0; j < PF; ++j) fetch(st[j], ti + j * NW);
+        fetch(st, ti);
     }
     SEGKV_PHASE_BEGIN;
     while (ti < n_tiles) {
-#pragma unroll
-        for (int j = 0; j < PF; ++j) {
-            if (ti < n_tiles) stage_to_lds(st[j]);
-            fetch(st[j], ti + PF * NW);
-            SEGKV_PHASE(0);
-            if (ti < n_tiles) process(ti);
-            ti += NW;
+        stage_to_lds(st);
+        const int nxt = claim_tile();
+        fetch(st, nxt);                                // while pending: nxt < 2*NW, a prompt tile
+        SEGKV_PHASE(0);
+        process(ti);
+        ti = nxt;
+        if (list_pending) {                            // every wave: once, after its first tile
+            resolve_list();
+            list_pending = false;
         }
     }
     SEGKV_PHASE_DUMP;
@@ -497,15 +500,15 @@ hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, unsigned grid, hi
 {
     switch (D) {
         case 64:
-            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<64, kMfmaWaves64, 1>), dim3(grid),
+            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<64, kMfmaWaves64>), dim3(grid),
                                dim3(kMfmaWaves64 * 64), 0, st, p);
             break;
         case 128:
-            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<128, kMfmaWaves128, 1>), dim3(grid),
+            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<128, kMfmaWaves128>), dim3(grid),
                                dim3(kMfmaWaves128 * 64), 0, st, p);
             break;
         case 256:
-            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<256, kMfmaWaves256, 1>), dim3(grid),
+            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<256, kMfmaWaves256>), dim3(grid),
                                dim3(kMfmaWaves256 * 64), 0, st, p);
             break;
         default:
