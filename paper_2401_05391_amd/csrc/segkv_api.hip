@@ -69,8 +69,16 @@ Plan make_plan(const segkv_dims* d)
         min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * (pl.nq < 32 ? pl.nq : 32));
     } else {
         pl.QB = (pl.nq == 1) ? 1 : 4;
-        pl.HP = env_int("SEGKV_HEADS_PER_WAVE", 4);
-        while (pl.HP > 1 && (d->Hkv % pl.HP != 0 || (pl.HP != 2 && pl.HP != 4))) pl.HP >>= 1;
+        // Adjacent KV heads per wave-wide load: 4 give 1 KB-contiguous reads,
+        // the best streaming shape, but also 4x fewer, 4x longer units.  Keep at
+        // least ~128 units; below that fall back to 2 or 1 heads per load
+        // (measured: GPT-J shape fastest with 2, batch-1 shapes with 1).
+        const int hp_env = env_int("SEGKV_HEADS_PER_WAVE", 0);
+        pl.HP = hp_env ? hp_env : 4;
+        while (pl.HP > 1 &&
+               (d->Hkv % pl.HP != 0 || (pl.HP != 2 && pl.HP != 4) ||
+                (!hp_env && (long)d->B * (d->Hkv / pl.HP) * ceil_div(pl.nq, pl.QB) < 128)))
+            pl.HP >>= 1;
         target_groups = env_int("SEGKV_TARGET_GROUPS", 1024);
         min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * pl.QB);
     }

@@ -385,18 +385,36 @@ __global__ __launch_bounds__(256) void sdpa_merge_kernel(_Float16* out, const fl
     if (gid >= (size_t)NQ * per_row) return;
     const size_t qidx = gid / per_row;
     const int d4 = (int)(gid % per_row) * 4;
+    // single pass, online: the (m, l) pairs and accumulator slices of four chunks
+    // are requested together so that their latencies overlap
     float mm = kEmptyMax;
-    for (int ch = 0; ch < n_chunks; ++ch)
-        mm = fmaxf(mm, ws_ml[((size_t)ch * NQ + qidx) * 2]);
     float ll = 0.0f;
     float4_t aa = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int ch = 0; ch < n_chunks; ++ch) {
-        const float2 ml = *reinterpret_cast<const float2*>(ws_ml + ((size_t)ch * NQ + qidx) * 2);
-        const float f = fast_exp2(ml.x - mm);
-        ll += ml.y * f;
-        const float4_t a =
-            *reinterpret_cast<const float4_t*>(ws_acc + ((size_t)ch * NQ + qidx) * D + d4);
-        aa += a * f;
+    for (int c0 = 0; c0 < n_chunks; c0 += 4) {
+        float2 ml[4];
+        float4_t a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int ch = min(c0 + u, n_chunks - 1);
+            ml[u] = *reinterpret_cast<const float2*>(ws_ml + ((size_t)ch * NQ + qidx) * 2);
+            a[u] = *reinterpret_cast<const float4_t*>(ws_acc + ((size_t)ch * NQ + qidx) * D + d4);
+        }
+        float m_new = mm;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (c0 + u < n_chunks) m_new = fmaxf(m_new, ml[u].x);
+        const float corr = fast_exp2(mm - m_new);
+        ll *= corr;
+        aa *= corr;
+        mm = m_new;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (c0 + u < n_chunks) {
+                const float f = fast_exp2(ml[u].x - mm);
+                ll += ml[u].y * f;
+                aa += a[u] * f;
+            }
+        }
     }
     const float inv = 1.0f / ll;
     half4_t o;
