@@ -101,7 +101,7 @@ void sdpa_decode_alu_kernel(SdpaParams p)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: tile bases stay uniform
     const int c = lane % LPR;            // 16-byte column of the row slice
     const int grp = lane / LPR;          // lane group
     const int hl = grp % HP;             // KV head within the block of HP heads
@@ -186,8 +186,7 @@ void sdpa_decode_alu_kernel(SdpaParams p)
     struct Tile {
         u32x4_t k[U][NV];
         u32x4_t v[U][NV];
-        int kpos[U];
-        uint32_t bmask[U];   // beams that see the row; 0 = row not valid
+        uint32_t meta[U];    // (key position << 8) | mask of beams that see the row (0 = invalid)
     };
 
     auto consume = [&](const Tile& t) {
@@ -206,8 +205,8 @@ void sdpa_decode_alu_kernel(SdpaParams p)
                     d = __builtin_amdgcn_fdot2(qv[qi][v * 4 + 3], as_half2(t.k[u][v].w), d, false);
                 }
                 d = group_allreduce_sum<LPR>(d);
-                const float zz = d * p.scale2 + slope2[qi] * (float)(t.kpos[u] - qpos);
-                const bool vis = (t.bmask[u] >> qbeam[qi]) & 1u;
+                const float zz = d * p.scale2 + slope2[qi] * (float)((int)(t.meta[u] >> 8) - qpos);
+                const bool vis = (t.meta[u] >> qbeam[qi]) & 1u;
                 z[u] = vis ? zz : -INFINITY;
                 m_new = fmaxf(m_new, z[u]);
             }
@@ -242,20 +241,25 @@ void sdpa_decode_alu_kernel(SdpaParams p)
     // ---- prompt segment (Section 3.3: loop over the prompt keys, FlashAttention style) ----
     if (k1 > k0) {
         const int n_tiles = (k1 - k0 + TILE - 1) / TILE;
+        // (scalar tile base) + (32-bit lane offset): no 64-bit address per load
+        const uint32_t row_stride = (uint32_t)p.Hkv * D;
+        const uint32_t lane_off = (uint32_t)hl * D + c * 8;
         auto fetch = [&](Tile& t, int ti) {
+            const int base = k0 + ti * TILE;
+            const int lim = min(TILE - 1, k1 - 1 - base);          // last valid row of the tile
+            const size_t tile_off = (((size_t)b * p.Lp + base) * p.Hkv + gb * HP) * D;
+            const _Float16* const kb = p.prompt_k + tile_off;
+            const _Float16* const vb = p.prompt_v + tile_off;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = k0 + ti * TILE + u * R + rl;
-                const bool ok = i < k1;
-                const int ic = ok ? i : (k1 - 1);
-                const size_t off = (((size_t)b * p.Lp + ic) * p.Hkv + g) * D + c * 8;
+                const int row = u * R + rl;
+                const uint32_t off = (uint32_t)min(row, lim) * row_stride + lane_off;
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
-                    t.k[u][v] = load16_stream(p.prompt_k + off + v * (LPR * 8));
-                    t.v[u][v] = load16_stream(p.prompt_v + off + v * (LPR * 8));
+                    t.k[u][v] = load16_stream(kb + off + v * (LPR * 8));
+                    t.v[u][v] = load16_stream(vb + off + v * (LPR * 8));
                 }
-                t.kpos[u] = ic;
-                t.bmask[u] = ok ? 0xffu : 0u;
+                t.meta[u] = ((uint32_t)(base + min(row, lim)) << 8) | (row <= lim ? 0xffu : 0u);
             }
         };
         stream_tiles_impl<Tile>(fetch, consume, wave, n_tiles);
@@ -294,8 +298,7 @@ void sdpa_decode_alu_kernel(SdpaParams p)
                     t.k[u][v] = load16_stream(kp + v * (LPR * 8));
                     t.v[u][v] = load16_stream(vp + v * (LPR * 8));
                 }
-                t.kpos[u] = p.Lp + s;
-                t.bmask[u] = ok ? (ent & 0xffu) : 0u;
+                t.meta[u] = ((uint32_t)(p.Lp + s) << 8) | (ok ? (ent & 0xffu) : 0u);
             }
         };
         stream_tiles_impl<Tile>(fetch, consume, wave, n_tiles);
