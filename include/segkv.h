@@ -118,6 +118,42 @@ size_t segkv_workspace_bytes(const segkv_dims* d);
 const char* segkv_status_string(int status);
 
 /*
+ * Segment-cache bookkeeping (Section 3.2).  Host-only arithmetic, no device.
+ *
+ * segkv_cache_token_bytes      Eq. (1): bytes of K and V of one token over all
+ *                              layers = 2 * L * H * D * elem_bytes.
+ * segkv_cache_standard_bytes   Eq. (2): contiguous per-beam cache
+ *                              BS * BW * (N_prompt + N_response) * token bytes.
+ * segkv_cache_segment_bytes    Eq. (3): prompt once per request plus the
+ *                              response buffer at its grown capacity,
+ *                              BS * (N_prompt + BW * capacity(N_response)) * token bytes.
+ * segkv_response_capacity      rows allocated for n_response valid rows: the
+ *                              response buffer grows in steps of 16 rows
+ *                              (capacity = ceil(n/16) * 16; 0 for n <= 0).
+ * All sizes are exact 64-bit integers; arguments <= 0 give 0.
+ */
+uint64_t segkv_cache_token_bytes(int32_t L, int32_t H, int32_t D, int32_t elem_bytes);
+uint64_t segkv_cache_standard_bytes(int32_t BS, int32_t BW, int32_t n_prompt, int32_t n_response,
+                                    uint64_t token_bytes);
+uint64_t segkv_cache_segment_bytes(int32_t BS, int32_t BW, int32_t n_prompt, int32_t n_response,
+                                   uint64_t token_bytes);
+int32_t segkv_response_capacity(int32_t n_response);
+
+/*
+ * Growth of the response buffers (Section 3.2: when the step count passes the
+ * capacity, a buffer 16 rows longer is allocated, the old rows are copied over
+ * and the old buffer is released).  The caller allocates and frees; this call
+ * copies rows 0..T-1 of old_k / old_v [Tcap_old, B*beam, Hkv, D] into new_k /
+ * new_v [Tcap_new, B*beam, Hkv, D] -- one contiguous block each, because the
+ * layout is sequence first.  Uses d->B, beam, Hkv, D and d->T (rows to copy,
+ * 0 <= T <= d->Tcap = Tcap_old); tcap_new >= d->Tcap.  Rows >= T of the new
+ * buffers are left untouched.  Device pointers, 16-byte aligned; asynchronous
+ * on `stream`.
+ */
+int segkv_grow_response(void* new_k, void* new_v, const void* old_k, const void* old_v,
+                        int32_t tcap_new, const segkv_dims* d, void* stream);
+
+/*
  * Measurement helper: reads `bytes` bytes (multiple of 16) from `src` with
  * 128-bit loads spread over the whole device and writes one checksum word per
  * work-group to `sink` (>= 4096 * 4 bytes).  Gives the practical streaming-read

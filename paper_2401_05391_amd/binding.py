@@ -22,7 +22,9 @@ SEGKV_WORKSPACE_TOO_SMALL = -4
 SEGKV_HIP_ERROR = -5
 
 EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
-           "segkv_status_string", "segkv_stream_read_probe")
+           "segkv_status_string", "segkv_stream_read_probe", "segkv_cache_token_bytes",
+           "segkv_cache_standard_bytes", "segkv_cache_segment_bytes", "segkv_response_capacity",
+           "segkv_grow_response")
 
 
 class SegkvDims(ctypes.Structure):
@@ -63,6 +65,17 @@ def load_library():
     lib.segkv_status_string.argtypes = [ctypes.c_int]
     lib.segkv_stream_read_probe.restype = ctypes.c_int
     lib.segkv_stream_read_probe.argtypes = [vp, sz, vp, vp]
+    u64 = ctypes.c_uint64
+    lib.segkv_cache_token_bytes.restype = u64
+    lib.segkv_cache_token_bytes.argtypes = [i32, i32, i32, i32]
+    lib.segkv_cache_standard_bytes.restype = u64
+    lib.segkv_cache_standard_bytes.argtypes = [i32, i32, i32, i32, u64]
+    lib.segkv_cache_segment_bytes.restype = u64
+    lib.segkv_cache_segment_bytes.argtypes = [i32, i32, i32, i32, u64]
+    lib.segkv_response_capacity.restype = i32
+    lib.segkv_response_capacity.argtypes = [i32]
+    lib.segkv_grow_response.restype = ctypes.c_int
+    lib.segkv_grow_response.argtypes = [vp, vp, vp, vp, i32, dp, vp]
     _lib = lib
     return lib
 
@@ -131,6 +144,31 @@ def prepare_sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims
         if rc != SEGKV_OK:
             raise SegkvError(rc, "segkv_sdpa_decode")
     return call
+
+
+def cache_token_bytes(L: int, H: int, D: int, elem_bytes: int = 2) -> int:
+    return int(load_library().segkv_cache_token_bytes(L, H, D, elem_bytes))
+
+
+def cache_standard_bytes(BS: int, BW: int, n_prompt: int, n_response: int, token_bytes: int) -> int:
+    return int(load_library().segkv_cache_standard_bytes(BS, BW, n_prompt, n_response, token_bytes))
+
+
+def cache_segment_bytes(BS: int, BW: int, n_prompt: int, n_response: int, token_bytes: int) -> int:
+    return int(load_library().segkv_cache_segment_bytes(BS, BW, n_prompt, n_response, token_bytes))
+
+
+def response_capacity(n_response: int) -> int:
+    return int(load_library().segkv_response_capacity(n_response))
+
+
+def grow_response(new_k, new_v, old_k, old_v, dims: SegkvDims, stream=None) -> None:
+    """Copy the valid rows of the old response buffers into larger new ones."""
+    rc = load_library().segkv_grow_response(_ptr(new_k), _ptr(new_v), _ptr(old_k), _ptr(old_v),
+                                            int(new_k.shape[0]), ctypes.byref(dims),
+                                            _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_grow_response")
 
 
 def stream_read_probe(src, sink, stream=None) -> None:

@@ -29,6 +29,8 @@ int env_int(const char* name, int fallback)
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+constexpr int kResponseGrowthStep = 16;   // Section 3.2: response capacity grows by 16 rows
+
 bool dims_ok(const segkv_dims* d)
 {
     return d && d->B >= 1 && d->beam >= 1 && d->Hkv >= 1 && d->Hq >= 1 && d->Hq % d->Hkv == 0 &&
@@ -225,6 +227,49 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
         if (e != hipSuccess) return SEGKV_HIP_ERROR;
     }
     return SEGKV_OK;
+}
+
+uint64_t segkv_cache_token_bytes(int32_t L, int32_t H, int32_t D, int32_t elem_bytes)
+{
+    if (L <= 0 || H <= 0 || D <= 0 || elem_bytes <= 0) return 0;
+    return 2ull * (uint64_t)L * (uint64_t)H * (uint64_t)D * (uint64_t)elem_bytes;
+}
+
+int32_t segkv_response_capacity(int32_t n_response)
+{
+    if (n_response <= 0) return 0;
+    return (int32_t)(((int64_t)n_response + kResponseGrowthStep - 1) / kResponseGrowthStep *
+                     kResponseGrowthStep);
+}
+
+uint64_t segkv_cache_standard_bytes(int32_t BS, int32_t BW, int32_t n_prompt, int32_t n_response,
+                                    uint64_t token_bytes)
+{
+    if (BS <= 0 || BW <= 0 || n_prompt < 0 || n_response < 0) return 0;
+    return (uint64_t)BS * (uint64_t)BW * ((uint64_t)n_prompt + (uint64_t)n_response) * token_bytes;
+}
+
+uint64_t segkv_cache_segment_bytes(int32_t BS, int32_t BW, int32_t n_prompt, int32_t n_response,
+                                   uint64_t token_bytes)
+{
+    if (BS <= 0 || BW <= 0 || n_prompt < 0 || n_response < 0) return 0;
+    const uint64_t cap = (uint64_t)segkv_response_capacity(n_response);
+    return (uint64_t)BS * ((uint64_t)n_prompt + (uint64_t)BW * cap) * token_bytes;
+}
+
+int segkv_grow_response(void* new_k, void* new_v, const void* old_k, const void* old_v,
+                        int32_t tcap_new, const segkv_dims* d, void* stream)
+{
+    if (!d || !new_k || !new_v || !old_k || !old_v) return SEGKV_INVALID_ARG;
+    if (d->B < 1 || d->beam < 1 || d->Hkv < 1 || d->D < 1) return SEGKV_INVALID_ARG;
+    if (d->T < 0 || d->T > d->Tcap || tcap_new < d->Tcap) return SEGKV_INVALID_ARG;
+    if ((d->D % 8) != 0) return SEGKV_UNSUPPORTED;
+    if (misaligned(new_k) || misaligned(new_v) || misaligned(old_k) || misaligned(old_v))
+        return SEGKV_MISALIGNED;
+    if (d->T == 0) return SEGKV_OK;
+    const size_t bytes = (size_t)d->T * d->B * d->beam * d->Hkv * d->D * 2;
+    const hipError_t e = segkv::launch_append_kv(new_k, new_v, old_k, old_v, bytes, (hipStream_t)stream);
+    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
 }
 
 int segkv_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream)
