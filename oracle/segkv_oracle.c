@@ -212,3 +212,65 @@ int segkv_oracle_sdpa_decode(double *out, double *probs, int32_t *anc,
     }
     return 0;
 }
+
+/*
+ * Prefill-phase attention (Section 3.1, prefill phase; Section 3.3: "a special
+ * case of that at decoding phase", using only the query and the prompt
+ * key/value).  Batch-first tensors, one softmax per (request, token, head):
+ *   q, out   [B, N0, Hq, D]      k, v   [B, N0, Hkv, D]
+ * Token i attends to keys 0..i of its own request (causal).  ALiBi and the
+ * grouped-query head map are read as in the decode oracle.  `rows` selects
+ * (b, i, hq) triples to compute (NULL = all, natural order); out is
+ * [n_rows][D] double.  Returns 0, or -1 on invalid dimensions.
+ */
+int segkv_oracle_sdpa_prefill(double *out, const uint16_t *q, const uint16_t *k,
+                              const uint16_t *v, const double *slopes, double scale,
+                              int32_t B, int32_t N0, int32_t Hq, int32_t Hkv, int32_t D,
+                              const int32_t *rows, int64_t n_rows)
+{
+    if (B < 1 || N0 < 1 || Hq < 1 || Hkv < 1 || D < 1 || Hq % Hkv != 0) return -1;
+    const int32_t group = Hq / Hkv;
+    if (!rows) n_rows = (int64_t)B * N0 * Hq;
+    half_table_init();
+
+#pragma omp parallel
+    {
+        double *z = (double *)malloc((size_t)N0 * sizeof(double));
+        double *qd = (double *)malloc((size_t)D * sizeof(double));
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t r = 0; r < n_rows; ++r) {
+            int32_t b, i, hq;
+            if (rows) {
+                b = rows[3 * r]; i = rows[3 * r + 1]; hq = rows[3 * r + 2];
+            } else {
+                hq = (int32_t)(r % Hq);
+                i = (int32_t)((r / Hq) % N0);
+                b = (int32_t)(r / ((int64_t)Hq * N0));
+            }
+            const int32_t g = hq / group;
+            const double slope = slopes ? slopes[hq] : 0.0;
+            for (int32_t e = 0; e < D; ++e)
+                qd[e] = half_bits_to_double(q[(((size_t)b * N0 + i) * Hq + hq) * D + e]);
+            double zmax = -INFINITY;
+            for (int32_t j = 0; j <= i; ++j) {
+                const uint16_t *kr = k + (((size_t)b * N0 + j) * Hkv + g) * D;
+                double dot = 0.0;
+                for (int32_t e = 0; e < D; ++e) dot += qd[e] * half_bits_to_double(kr[e]);
+                z[j] = scale * dot + slope * (double)j;
+                if (z[j] > zmax) zmax = z[j];
+            }
+            double denom = 0.0;
+            for (int32_t j = 0; j <= i; ++j) { z[j] = exp(z[j] - zmax); denom += z[j]; }
+            double *o = out + (size_t)r * D;
+            for (int32_t e = 0; e < D; ++e) o[e] = 0.0;
+            for (int32_t j = 0; j <= i; ++j) {
+                const uint16_t *vr = v + (((size_t)b * N0 + j) * Hkv + g) * D;
+                const double w = z[j] / denom;
+                for (int32_t e = 0; e < D; ++e) o[e] += w * half_bits_to_double(vr[e]);
+            }
+        }
+        free(z);
+        free(qd);
+    }
+    return 0;
+}

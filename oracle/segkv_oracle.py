@@ -45,6 +45,7 @@ def _load():
         lib.segkv_oracle_append_kv.restype = ctypes.c_int
         lib.segkv_oracle_sdpa_decode.restype = ctypes.c_int
         lib.segkv_oracle_ancestors.restype = None
+        lib.segkv_oracle_sdpa_prefill.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -122,3 +123,27 @@ def sdpa_decode(q: np.ndarray, prompt_k: np.ndarray, prompt_v: np.ndarray,
     if rc != 0:
         raise ValueError("sdpa_decode: invalid dimensions")
     return out, anc, probs
+
+
+def sdpa_prefill(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
+                 slopes: Optional[np.ndarray] = None, rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """fp64 causal prefill attention.  q [B,N0,Hq,D], k/v [B,N0,Hkv,D] fp16.
+    Returns [B,N0,Hq,D] float64, or [len(rows), D] for rows = [[b, i, hq], ...]."""
+    B, N0, Hq, D = q.shape
+    Hkv = k.shape[2]
+    assert k.shape == (B, N0, Hkv, D) and v.shape == k.shape
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 3)
+        n = rows.shape[0]
+        out = np.empty((n, D), dtype=np.float64)
+    else:
+        n = B * N0 * Hq
+        out = np.empty((B, N0, Hq, D), dtype=np.float64)
+    sl = None if slopes is None else np.ascontiguousarray(slopes, dtype=np.float64)
+    rc = _load().segkv_oracle_sdpa_prefill(
+        _p(out), _p(_u16(q)), _p(_u16(k)), _p(_u16(v)), _p(sl), ctypes.c_double(scale),
+        ctypes.c_int32(B), ctypes.c_int32(N0), ctypes.c_int32(Hq), ctypes.c_int32(Hkv),
+        ctypes.c_int32(D), _p(rows), ctypes.c_int64(n))
+    if rc != 0:
+        raise ValueError("sdpa_prefill: invalid dimensions")
+    return out
