@@ -118,6 +118,22 @@ size_t segkv_workspace_bytes(const segkv_dims* d);
 const char* segkv_status_string(int status);
 
 /*
+ * Prefill-phase attention (Section 3.1, prefill phase; Section 3.3: the special
+ * case of the decode kernel that uses only the query and the prompt key/value).
+ * Batch-first tensors in and out, no transposes:
+ *   out, q   [B, Lp, Hq, D]  fp16        k, v   [B, Lp, Hkv, D]  fp16
+ * k and v are the prompt segment itself: after this call they are what
+ * segkv_sdpa_decode takes as prompt_k / prompt_v.  Token i of a request attends
+ * to keys 0..i of the same request (causal); beams are not expanded yet.
+ * alibi_slopes (NULL or [Hq] fp32) and scale as in segkv_sdpa_decode; key j has
+ * position j.  Uses d->B, Hq, Hkv, D and d->Lp (>= 1); beam, T, Tcap are ignored.
+ * Arithmetic: fp16 operands on the matrix cores, fp32 softmax and accumulation,
+ * softmax weights rounded to fp16 for the PV product, fp16 output (RNE).
+ */
+int segkv_sdpa_prefill(void* out, const void* q, const void* k, const void* v,
+                       const float* alibi_slopes, float scale, const segkv_dims* d, void* stream);
+
+/*
  * Segment-cache bookkeeping (Section 3.2).  Host-only arithmetic, no device.
  *
  * segkv_cache_token_bytes      Eq. (1): bytes of K and V of one token over all

@@ -24,7 +24,7 @@ SEGKV_HIP_ERROR = -5
 EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_status_string", "segkv_stream_read_probe", "segkv_cache_token_bytes",
            "segkv_cache_standard_bytes", "segkv_cache_segment_bytes", "segkv_response_capacity",
-           "segkv_grow_response")
+           "segkv_grow_response", "segkv_sdpa_prefill")
 
 
 class SegkvDims(ctypes.Structure):
@@ -74,6 +74,8 @@ def load_library():
     lib.segkv_cache_segment_bytes.argtypes = [i32, i32, i32, i32, u64]
     lib.segkv_response_capacity.restype = i32
     lib.segkv_response_capacity.argtypes = [i32]
+    lib.segkv_sdpa_prefill.restype = ctypes.c_int
+    lib.segkv_sdpa_prefill.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, dp, vp]
     lib.segkv_grow_response.restype = ctypes.c_int
     lib.segkv_grow_response.argtypes = [vp, vp, vp, vp, i32, dp, vp]
     _lib = lib
@@ -146,6 +148,13 @@ def prepare_sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims
     return call
 
 
+def sdpa_prefill(out, q, k, v, dims: SegkvDims, scale: float, alibi_slopes=None, stream=None) -> None:
+    rc = load_library().segkv_sdpa_prefill(_ptr(out), _ptr(q), _ptr(k), _ptr(v), _ptr(alibi_slopes),
+                                           float(scale), ctypes.byref(dims), _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_sdpa_prefill")
+
+
 def cache_token_bytes(L: int, H: int, D: int, elem_bytes: int = 2) -> int:
     return int(load_library().segkv_cache_token_bytes(L, H, D, elem_bytes))
 
@@ -168,7 +177,7 @@ def grow_response(new_k, new_v, old_k, old_v, dims: SegkvDims, stream=None) -> N
                                             int(new_k.shape[0]), ctypes.byref(dims),
                                             _stream_handle(stream))
     if rc != SEGKV_OK:
-        raise SegkvError(rc, "segkv_grow_response")
+        raise SegkvError(rc, "segkv_grow_response", "segkv_sdpa_prefill")
 
 
 def stream_read_probe(src, sink, stream=None) -> None:

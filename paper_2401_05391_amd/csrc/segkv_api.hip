@@ -229,6 +229,29 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
     return SEGKV_OK;
 }
 
+int segkv_sdpa_prefill(void* out, const void* q, const void* k, const void* v,
+                       const float* alibi_slopes, float scale, const segkv_dims* d, void* stream)
+{
+    if (!d || !out || !q || !k || !v) return SEGKV_INVALID_ARG;
+    if (d->B < 1 || d->Hkv < 1 || d->Hq < 1 || d->Hq % d->Hkv != 0 || d->D < 1 || d->Lp < 1)
+        return SEGKV_INVALID_ARG;
+    if (d->D != 64 && d->D != 128 && d->D != 256) return SEGKV_UNSUPPORTED;
+    if ((long)d->B * d->Hq * ((d->Lp + 127) / 128) > (1L << 30)) return SEGKV_UNSUPPORTED;
+    if (misaligned(out) || misaligned(q) || misaligned(k) || misaligned(v) ||
+        ((uintptr_t)alibi_slopes & 3u))
+        return SEGKV_MISALIGNED;
+    segkv::PrefillParams p{};
+    p.q = (const _Float16*)q;
+    p.k = (const _Float16*)k;
+    p.v = (const _Float16*)v;
+    p.out = (_Float16*)out;
+    p.slopes = alibi_slopes;
+    p.scale2 = scale * 1.4426950408889634f;
+    p.B = d->B; p.N0 = d->Lp; p.Hq = d->Hq; p.Hkv = d->Hkv; p.G = d->Hq / d->Hkv;
+    const hipError_t e = segkv::launch_sdpa_prefill(p, d->D, (hipStream_t)stream);
+    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+}
+
 uint64_t segkv_cache_token_bytes(int32_t L, int32_t H, int32_t D, int32_t elem_bytes)
 {
     if (L <= 0 || H <= 0 || D <= 0 || elem_bytes <= 0) return 0;

@@ -36,6 +36,16 @@ struct SdpaParams {
 };
 
 
+struct PrefillParams {
+    const _Float16* q;    // [B, N0, Hq, D]
+    const _Float16* k;    // [B, N0, Hkv, D]
+    const _Float16* v;    // [B, N0, Hkv, D]
+    _Float16* out;        // [B, N0, Hq, D]
+    const float* slopes;  // [Hq] or null
+    float scale2;         // scale * log2(e)
+    int B, N0, Hq, Hkv, G;
+};
+
 constexpr int kMaxStepsPerChunk = 256;   // response steps one work-group can resolve
 constexpr int kMaxListEntries = 1024;    // (step, slot) rows of one chunk: steps * beam <= this
 constexpr int kMfmaWaves64 = 8;           // waves per work-group of the MFMA kernel, by head dim
@@ -46,6 +56,7 @@ constexpr int kProbeGroups = 4096;       // work-groups (and sink words) of the 
 hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, int HP, unsigned grid,
                               hipStream_t st);
 hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, unsigned grid, hipStream_t st);
+hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st);
 hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_acc, int NQ, int D,
                              int n_chunks, hipStream_t st);
 hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const void* src_v,

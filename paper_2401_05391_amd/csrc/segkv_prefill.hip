@@ -1,0 +1,236 @@
+// libsegkv device code: prefill-phase attention (arxiv 2401.05391, Section 3.1
+// prefill phase and Section 3.3: "a special case of [the decode kernel], only
+// using input tensors of query and prompt key/value").  Batch-first tensors,
+// no transposes: q/out [B, N0, Hq, D], k/v [B, N0, Hkv, D]; k/v ARE the prompt
+// segment that the decode kernel reads afterwards.  Causal: token i sees keys
+// 0..i of its own request.
+//
+// Compute-bound, so everything runs on the matrix cores, with the same operand
+// orientation as the decode kernel:
+//     S^T[key][query]  = K[key][:]   . Q^T[:][query]
+//     O^T[d][query]   += V^T[d][key] . P^T[key][query]
+// A work-group of 4 waves owns 128 consecutive query tokens of one (request,
+// query head); each wave holds 32 of them as the N dimension (Q^T operand in
+// registers) and walks the key tiles 0 .. its own diagonal.  K/V tiles of 32
+// keys are staged once per work-group into double-buffered LDS (one barrier
+// per tile) and read by all four waves; the V^T operand comes out of LDS with
+// the transposing read.  Later query blocks have more keys to visit, so they
+// are scheduled first.
+#include "segkv_common.h"
+#include "segkv_launch.h"
+#include "segkv_device.h"
+#include "segkv_mfma_tile.h"
+
+namespace segkv {
+
+constexpr int kPrefillWaves = 4;
+constexpr int kPrefillQueries = kPrefillWaves * kQueryTile;   // query tokens per work-group
+
+// Two work-groups per CU (two waves per SIMD) for D <= 128, so that one wave's
+// softmax arithmetic overlaps the other's MFMAs.
+template <int D>
+__global__ __launch_bounds__(kPrefillWaves * 64) __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1)))
+void sdpa_prefill_mfma_kernel(PrefillParams p)
+{
+    using Geo = MfmaGeometry<D>;
+    constexpr int CPR = Geo::CPR, NKS = Geo::NKS, NDB = Geo::NDB;
+    constexpr int ROWB = Geo::ROWB, VROWB = Geo::VROWB, TILEB = Geo::TILEB, VTILEB = Geo::VTILEB;
+    constexpr int NT = kPrefillWaves * 64;
+    constexpr int STAGEB = TILEB + VTILEB;
+    constexpr int kVecPerTile = kKeyTile * CPR;            // 16-byte vectors of one operand tile
+    constexpr int kVecPerThread = (kVecPerTile + NT - 1) / NT;
+    constexpr int OROWB = D * 2 + 16;                      // output staging row pitch
+
+    __shared__ __align__(16) unsigned char s_stage[2][STAGEB];
+    static_assert(2 * STAGEB >= kPrefillWaves * kQueryTile * OROWB, "output staging reuses the tiles");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31;
+    const int h = lane >> 5;
+
+    // ---- work item: heavy (late) query blocks first ----
+    const int n_qblocks = (p.N0 + kPrefillQueries - 1) / kPrefillQueries;
+    int id = xcd_contiguous_index(blockIdx.x, gridDim.x);
+    const int hq = id % p.Hq;                 id /= p.Hq;
+    const int b = id % p.B;                   id /= p.B;
+    const int qblk = n_qblocks - 1 - id;
+    const int g = hq / p.G;
+    const int q0 = qblk * kPrefillQueries;
+    const int wq0 = q0 + wave * kQueryTile;   // first query token of this wave
+    const int qi = wq0 + n;                   // this lane's query token
+    const float slope2 = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
+
+    // ---- Q^T operand: this lane's query row, 8 halves per k-step, in registers ----
+    half8_t qreg[NKS];
+    {
+        const int qrow = min(qi, p.N0 - 1);
+        const _Float16* qp = p.q + (((size_t)b * p.N0 + qrow) * p.Hq + hq) * D;
+#pragma unroll
+        for (int t = 0; t < NKS; ++t)
+            qreg[t] = __builtin_bit_cast(half8_t, load16(qp + 16 * t + 8 * h));
+    }
+
+    // ---- cooperative K/V tile staging ----
+    const int k_end = min(q0 + kPrefillQueries, p.N0);     // keys this block may need
+    const int n_tiles = (k_end + kKeyTile - 1) / kKeyTile;
+    const uint32_t row_stride = (uint32_t)p.Hkv * D;
+    u32x4_t sk[kVecPerThread], sv[kVecPerThread];
+    auto fetch = [&](int ti) __attribute__((always_inline)) {
+        const int base = ti * kKeyTile;
+        const int lim = min(kKeyTile - 1, p.N0 - 1 - base);
+        const size_t tile_off = (((size_t)b * p.N0 + base) * p.Hkv + g) * D;
+        const _Float16* const kb = p.k + tile_off;
+        const _Float16* const vb = p.v + tile_off;
+#pragma unroll
+        for (int c = 0; c < kVecPerThread; ++c) {
+            const int i = tid + c * NT;
+            const int row = min((i / CPR) % kKeyTile, lim);
+            const uint32_t off = (uint32_t)row * row_stride + (i % CPR) * 8;
+            sk[c] = load16(kb + off);
+            sv[c] = load16(vb + off);
+        }
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < kVecPerThread; ++c) {
+            const int i = tid + c * NT;
+            if (i < kVecPerTile) {
+                const int row = i / CPR, ch = i % CPR;
+                *reinterpret_cast<u32x4_t*>(s_stage[buf] + row * ROWB + (ch << 4)) = sk[c];
+                *reinterpret_cast<u32x4_t*>(s_stage[buf] + TILEB + row * VROWB + (ch << 4)) = sv[c];
+            }
+        }
+    };
+
+    // ---- running state ----
+    float m_ref = kEmptyMax;
+    float l_part = 0.0f;
+    float16_t o_acc[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.0f;
+
+    const int grp = lane >> 4;
+    const int li = lane & 15;
+    const int tr_base = (4 * h + (li >> 2)) * VROWB + ((16 * (grp & 1) + 4 * (li & 3)) << 1);
+
+    auto compute_tile = [&](const unsigned char* k_tile, const unsigned char* v_tile, int base,
+                            bool diagonal) __attribute__((always_inline)) {
+        float16_t s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < NKS; ++t) {
+            const half8_t a =
+                *reinterpret_cast<const half8_t*>(k_tile + n * ROWB + ((2 * t + h) << 4));
+            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
+        }
+        float m_tile = -INFINITY;
+        if (!diagonal && p.slopes == nullptr) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                s[r] *= p.scale2;
+                m_tile = fmaxf(m_tile, s[r]);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = base + 8 * (r >> 2) + 4 * h + (r & 3);
+                const float z = s[r] * p.scale2 + slope2 * (float)(key - qi);
+                s[r] = (key <= qi) ? z : -INFINITY;       // causal; also hides keys >= N0
+                m_tile = fmaxf(m_tile, s[r]);
+            }
+        }
+        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+        if (__any(m_tile > m_ref + kRescaleSlack)) {
+            const float m_new = fmaxf(m_ref, m_tile);
+            const float corr = fast_exp2(m_ref - m_new);
+            m_ref = m_new;
+            l_part *= corr;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[db][r] *= corr;
+        }
+        half8_t pb[2];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float pr = fast_exp2(s[r] - m_ref);
+            l_part += pr;
+            pb[r >> 3][r & 7] = (_Float16)pr;
+        }
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int off = tr_base + (16 * u) * VROWB + db * 64;
+                const half4_t lo = lds_read_tr16(v_tile + off);
+                const half4_t hi = lds_read_tr16(v_tile + off + 8 * VROWB);
+                const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
+            }
+            if (NDB > 4) __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- main loop over key tiles: one barrier per tile, loads one tile ahead ----
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int ti = 0; ti < n_tiles; ++ti) {
+        const int buf = ti & 1;
+        if (ti + 1 < n_tiles) fetch(ti + 1);
+        const int base = ti * kKeyTile;
+        // tiles entirely above this wave's last query are skipped (uniform per wave)
+        if (base <= wq0 + kQueryTile - 1)
+            compute_tile(s_stage[buf], s_stage[buf] + TILEB, base, base + kKeyTile - 1 > wq0);
+        if (ti + 1 < n_tiles) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- normalise, transpose through LDS, store rows with 128-bit writes ----
+    l_part += __shfl_xor(l_part, 32);
+    const float inv = 1.0f / l_part;
+    unsigned char* const obuf = &s_stage[0][0] + wave * (kQueryTile * OROWB);
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            half4_t o4;
+            o4.x = (_Float16)(o_acc[db][4 * i + 0] * inv);
+            o4.y = (_Float16)(o_acc[db][4 * i + 1] * inv);
+            o4.z = (_Float16)(o_acc[db][4 * i + 2] * inv);
+            o4.w = (_Float16)(o_acc[db][4 * i + 3] * inv);
+            *reinterpret_cast<half4_t*>(obuf + n * OROWB + ((32 * db + 8 * i + 4 * h) << 1)) = o4;
+        }
+    // the wave reads back only what it wrote itself
+    constexpr int kRowsPerPass = 64 / CPR;
+#pragma unroll
+    for (int r0 = 0; r0 < kQueryTile; r0 += kRowsPerPass) {
+        const int row = r0 + lane / CPR;
+        const int ch = lane % CPR;
+        const int tok = wq0 + row;
+        const u32x4_t w = *reinterpret_cast<const u32x4_t*>(obuf + row * OROWB + (ch << 4));
+        if (tok < p.N0)
+            store16(p.out + (((size_t)b * p.N0 + tok) * p.Hq + hq) * D + ch * 8, w);
+    }
+}
+
+hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
+{
+    const int n_qblocks = (p.N0 + kPrefillQueries - 1) / kPrefillQueries;
+    const unsigned grid = (unsigned)((size_t)p.B * p.Hq * n_qblocks);
+    const dim3 block(kPrefillWaves * 64);
+    switch (D) {
+        case 64:  hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, 0, st, p); break;
+        case 128: hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, 0, st, p); break;
+        case 256: hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, 0, st, p); break;
+        default:  return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace segkv

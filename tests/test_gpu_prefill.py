@@ -1,0 +1,117 @@
+"""GPU parity of the prefill attention against the fp64 oracle, and hand-over of
+its K/V to the decode kernel (prefill -> first decode step)."""
+import numpy as np
+import pytest
+
+from paper_2401_05391_amd.workloads import alibi_slopes
+from segkv_testlib import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw(B, N0, Hq, Hkv, D, seed):
+    rng = np.random.default_rng(seed)
+    f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
+    return f(B, N0, Hq, D), f(B, N0, Hkv, D), f(B, N0, Hkv, D)
+
+
+def _run(q, k, v, scale, slopes=None):
+    import torch
+    import paper_2401_05391_amd as segkv
+    dev = torch.device("cuda:0")
+    B, N0, Hq, D = q.shape
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    out = torch.full((B, N0, Hq, D), float("nan"), dtype=torch.float16, device=dev)
+    dims = segkv.make_dims(B, 1, Hq, k.shape[2], D, N0, 1, 1)
+    segkv.sdpa_prefill(out, up(q), up(k), up(v), dims, scale, alibi_slopes=up(slopes))
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+CASES = [
+    # B, N0, Hq, Hkv, D, alibi : several key tiles and query blocks, ragged tails
+    (1, 1, 1, 1, 64, False),
+    (2, 31, 2, 2, 64, False),
+    (2, 33, 4, 2, 128, False),
+    (1, 130, 4, 4, 128, True),
+    (2, 257, 8, 2, 128, False),
+    (1, 300, 2, 1, 256, False),
+    (3, 128, 2, 2, 64, True),
+    (1, 515, 2, 2, 128, False),
+]
+
+
+@pytest.mark.parametrize("B,N0,Hq,Hkv,D,alibi", CASES)
+def test_prefill_matches_oracle(B, N0, Hq, Hkv, D, alibi):
+    from oracle import segkv_oracle as oracle
+    print(f"\n[case] prefill B={B} N0={N0} Hq={Hq} Hkv={Hkv} D={D} alibi={alibi}", flush=True)
+    q, k, v = _draw(B, N0, Hq, Hkv, D, 1000 + N0)
+    slopes = alibi_slopes(Hq) if alibi else None
+    scale = 1.0 / np.sqrt(D)
+    ref = oracle.sdpa_prefill(q, k, v, scale, slopes=slopes)
+    got = _run(q, k, v, scale, slopes)
+    assert_parity(got, ref, f"prefill N0={N0} D={D}")
+
+
+def test_prefill_is_deterministic_and_ignores_future_keys():
+    q, k, v = _draw(2, 200, 4, 2, 128, 7)
+    a = _run(q, k, v, 0.088)
+    b = _run(q, k, v, 0.088)
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+    k2, v2 = k.copy(), v.copy()
+    k2[:, 150:] = 60000
+    v2[:, 150:] = -60000
+    c = _run(q, k2, v2, 0.088)
+    # (not bit-identical: lanes that do see the huge keys move the wave's shared
+    # rescale points, which changes the rounding of their neighbours)
+    from oracle import segkv_oracle as oracle
+    ref = oracle.sdpa_prefill(q, k, v, 0.088)
+    assert_parity(c[:, :150], ref[:, :150], "tokens before the poisoned keys")
+    assert np.max(np.abs(a[:, :150].astype(np.float64) - c[:, :150].astype(np.float64))) <= 1e-3
+
+
+def test_llama2_7b_prompt_shape_sampled_rows():
+    # full benchmark shape (one request batch of 4), oracle on sampled rows
+    from oracle import segkv_oracle as oracle
+    B, N0, Hq, Hkv, D = 4, 1024, 32, 32, 128
+    print("\n[case] prefill llama2-7b shape", flush=True)
+    q, k, v = _draw(B, N0, Hq, Hkv, D, 99)
+    scale = 1.0 / np.sqrt(D)
+    got = _run(q, k, v, scale)
+    rng = np.random.default_rng(5)
+    rows = np.stack([rng.integers(0, B, 600), rng.integers(0, N0, 600), rng.integers(0, Hq, 600)], 1)
+    rows[:8, 1] = [0, 1, 31, 32, 127, 128, 1022, 1023]
+    ref = oracle.sdpa_prefill(q, k, v, scale, rows=rows.astype(np.int32))
+    sel = got[rows[:, 0], rows[:, 1], rows[:, 2]]
+    assert_parity(sel, ref, "prefill 7b sampled")
+
+
+def test_prefill_then_first_decode_step_share_the_prompt_segment():
+    # K/V given to prefill are handed unchanged to the decode kernel as the
+    # prompt segment; the decode step (beam 1, T = 1) at position N0 must match
+    # the oracle's prefill over N0 + 1 tokens at its last token.
+    import torch
+    import paper_2401_05391_amd as segkv
+    from oracle import segkv_oracle as oracle
+    B, N0, Hq, Hkv, D = 2, 96, 4, 2, 128
+    q, k, v = _draw(B, N0 + 1, Hq, Hkv, D, 11)
+    scale = 1.0 / np.sqrt(D)
+    ref = oracle.sdpa_prefill(q, k, v, scale)
+    dev = torch.device("cuda:0")
+    pk = torch.from_numpy(np.ascontiguousarray(k[:, :N0])).to(dev)
+    pv = torch.from_numpy(np.ascontiguousarray(v[:, :N0])).to(dev)
+    pq = torch.from_numpy(np.ascontiguousarray(q[:, :N0])).to(dev)
+    out_p = torch.empty((B, N0, Hq, D), dtype=torch.float16, device=dev)
+    segkv.sdpa_prefill(out_p, pq, pk, pv, segkv.make_dims(B, 1, Hq, Hkv, D, N0, 1, 1), scale)
+    rk = torch.full((16, B, Hkv, D), float("nan"), dtype=torch.float16, device=dev)
+    rv = torch.full((16, B, Hkv, D), float("nan"), dtype=torch.float16, device=dev)
+    out_d = torch.empty((B, Hq, D), dtype=torch.float16, device=dev)
+    dims = segkv.make_dims(B, 1, Hq, Hkv, D, N0, 1, 16)
+    nb = segkv.workspace_bytes(dims)
+    ws = torch.empty(max(nb, 16) // 4, dtype=torch.float32, device=dev) if nb else None
+    segkv.sdpa_decode(out_d, torch.from_numpy(np.ascontiguousarray(q[:, N0])).to(dev), pk, pv, rk, rv,
+                      None, dims, scale, k_new=torch.from_numpy(np.ascontiguousarray(k[:, N0])).to(dev),
+                      v_new=torch.from_numpy(np.ascontiguousarray(v[:, N0])).to(dev), workspace=ws)
+    torch.cuda.synchronize()
+    assert_parity(out_p.cpu().numpy(), ref[:, :N0], "prefill part")
+    assert_parity(out_d.cpu().numpy(), ref[:, N0], "first decode step")
