@@ -58,6 +58,7 @@ struct ResponseListSmem {
     int wave_cnt[kListThreads / 64];
     uint32_t ent[kMaxListEntries];
     int total;
+    int ready;                         // single-wave builder: set (release) once ent/total are final
 };
 
 // One step's parent slots of request b, as loaded (not yet packed), so that a
@@ -203,6 +204,150 @@ __device__ void build_response_list(ResponseListSmem& sm, const int32_t* parent,
                 anc_out[(size_t)(s0 + t) * N + (size_t)b * W + j] = (int32_t)map_get(A, j);
     }
     __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// The same list built by ONE wave, with no work-group barrier: the other waves
+// of the group keep streaming prompt tiles meanwhile and pick the list up
+// through `ready` when they reach their first response tile.
+// Lane i owns the local steps 4i..4i+3 of the chunk (kMaxStepsPerChunk = 256).
+// ---------------------------------------------------------------------------
+constexpr int kListStepsPerLane = kMaxStepsPerChunk / 64;
+
+struct ListRows {
+    ParentRow r[kListStepsPerLane];
+};
+
+// Requests the parent rows the builder lane needs (step s0+t+1 for its steps
+// t < n-1); other slots are pointed at the last valid row and ignored later, so
+// that no load is conditional.  Requires W > 1 (parent non-null) and T >= 1.
+__device__ __forceinline__ void load_list_rows(ListRows& rows, const int32_t* parent, int N, int W,
+                                               int T, int b, int s0, int lane)
+{
+#pragma unroll
+    for (int k = 0; k < kListStepsPerLane; ++k) {
+        const int s = min(s0 + kListStepsPerLane * lane + k + 1, T - 1);
+        rows.r[k] = load_parent_row(parent, N, W, b, s);
+    }
+}
+
+// Inclusive suffix composition over the lanes of a wave: lane i ends up with
+// x_i o x_{i+1} o ... o x_63.
+__device__ __forceinline__ uint32_t wave_suffix_compose(uint32_t x, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_down(x, off);
+        if (lane + off < 64) x = map_compose(x, o);
+    }
+    return x;
+}
+
+// Called by all 64 lanes of exactly one wave.  `rows` from load_list_rows()
+// (ignored when W == 1).  Ends with a release store to sm.ready.
+__device__ void build_response_list_wave(ResponseListSmem& sm, const int32_t* parent,
+                                         int32_t* anc_out, int B, int W, int T, int b, int s0,
+                                         int s1, const ListRows& rows, int lane)
+{
+    constexpr int SPL = kListStepsPerLane;
+    const int n = s1 - s0;
+    const int N = B * W;
+    if (W == 1) {
+#pragma unroll
+        for (int k = 0; k < SPL; ++k) {
+            const int t = SPL * lane + k;
+            if (t < n) {
+                sm.ent[t] = ((uint32_t)t << 16) | 1u;
+                if (anc_out) anc_out[(size_t)(s0 + t) * N + b] = 0;
+            }
+        }
+        if (lane == 0) sm.total = n;
+        __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return;
+    }
+
+    // (1) carry = A_{s1-1} = P_{s1} o ... o P_{T-1}
+    uint32_t carry = kIdentityMap;
+    const int later = T - s1;
+    if (later > 0) {
+        const int per = (later + 63) / 64;
+        const int lo = s1 + lane * per;
+        const int hi = min(lo + per, T);
+        uint32_t c = kIdentityMap;
+        for (int s = lo; s < hi; ++s) c = map_compose(c, load_parent_map(parent, N, W, b, s));
+        carry = __shfl(wave_suffix_compose(c, lane), 0);
+    }
+
+    // (2) y_t = P_{s0+t+1} (t < n-1), y_{n-1} = carry; A_t = y_t o y_{t+1} o ... o y_{n-1}
+    uint32_t suf[SPL];                                 // suffix inside the lane
+#pragma unroll
+    for (int k = SPL - 1; k >= 0; --k) {
+        const int t = SPL * lane + k;
+        uint32_t y = kIdentityMap;
+        if (t < n - 1) y = pack_parent_row(rows.r[k], W);
+        else if (t == n - 1) y = carry;
+        suf[k] = (k == SPL - 1) ? y : map_compose(y, suf[k + 1]);
+    }
+    const uint32_t incl = wave_suffix_compose(suf[0], lane);
+    uint32_t after = __shfl_down(incl, 1);             // composition of all later lanes
+    if (lane == 63) after = kIdentityMap;
+
+    // (3) distinct slots per step, exclusive prefix sum of their counts
+    uint32_t A[SPL], present[SPL];
+    int mine = 0;
+#pragma unroll
+    for (int k = 0; k < SPL; ++k) {
+        A[k] = (k == 0) ? incl : map_compose(suf[k], after);
+        present[k] = 0;
+        if (SPL * lane + k < n) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < W) present[k] |= 1u << map_get(A[k], j);
+        }
+        mine += __popc(present[k]);
+    }
+    int c = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(c, off);
+        if (lane >= off) c += o;
+    }
+    int pos = c - mine;
+    if (lane == 63) sm.total = c;
+
+    // (4) entries, and the resolved table if asked for
+#pragma unroll
+    for (int k = 0; k < SPL; ++k) {
+        const int t = SPL * lane + k;
+        if (t < n) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (present[k] & (1u << u)) {
+                    uint32_t mask = 0;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (j < W && map_get(A[k], j) == (uint32_t)u) mask |= 1u << j;
+                    sm.ent[pos++] = ((uint32_t)t << 16) | ((uint32_t)u << 8) | mask;
+                }
+            }
+            if (anc_out) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (j < W)
+                        anc_out[(size_t)(s0 + t) * N + (size_t)b * W + j] = (int32_t)map_get(A[k], j);
+            }
+        }
+    }
+    __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Any other wave: blocks until the builder wave has published the list (the
+// builder never waits for anything, so this ends), returns the row count.
+__device__ __forceinline__ int wait_response_list(ResponseListSmem& sm)
+{
+    while (__hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
+        __builtin_amdgcn_s_sleep(2);
+    return sm.total;
 }
 
 }  // namespace segkv

@@ -130,9 +130,12 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
             qw[c] = load16(p.q + row * D + ch * 8);
         }
     }
-    const bool has_row = (s1 > s0) && list_thread_has_row(p.W, s0, s1);
-    ParentRow prow;
-    if (has_row) prow = load_parent_row(p.parent, N, p.W, b, s0 + tid + 1);
+    // One wave (the last) resolves the response list on its own while the others
+    // stream prompt tiles; its parent rows are requested here, with the Q chunks.
+    const bool has_resp = s1 > s0;                              // uniform over the work-group
+    const bool is_builder = has_resp && wave == NW - 1;         // uniform over the wave
+    ListRows lrows;
+    if (is_builder && p.W > 1) load_list_rows(lrows, p.parent, N, p.W, p.T, b, s0, lane);
 
     // ---- fused append: the block that owns step T-1 copies the unit's new rows ----
     const bool have_new = (p.k_new != nullptr);
@@ -306,23 +309,18 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         for (int i = 0; i < NLD; ++i) st.v[i] = load16(dummy);
     };
 
-    // The response list is resolved by the whole work-group (it has barriers).
-    // With enough prompt tiles it runs after each wave's first tile, when the
-    // parent rows requested above have long arrived and the next tile is in
-    // flight; otherwise right away.
+    // The response list comes from the builder wave; a wave asks for it when it
+    // first claims a tile past the prompt tiles (by then it is long finished).
     int total = 0;
     int n_tiles = n_ptiles;
-    uint32_t own_map = kIdentityMap;
-    auto resolve_list = [&]() {
-        if (s1 > s0) {
-            build_response_list(s_list, p.parent, (g == 0 && qb == 0) ? p.anc_out : nullptr, p.B,
-                                p.W, p.T, b, s0, s1, own_map);
-            total = s_list.total;
+    bool list_known = !has_resp;
+    auto need_list = [&]() {
+        if (!list_known) {
+            total = wait_response_list(s_list);
             n_tiles = n_ptiles + (total + kKeyTile - 1) / kKeyTile;
+            list_known = true;
         }
-        SEGKV_STAMP(2);
     };
-    const bool late_list = n_ptiles >= 2 * NW;         // uniform over the work-group
     auto claim_tile = [&]() {
         int v = 0;
         if (lane == 0) v = atomicAdd(&s_next_tile, 1);
@@ -364,38 +362,43 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     };
 
     Staged st;
-    int ti = wave;                                     // first tile of every wave is its own index
-    if (tid == 0) s_next_tile = NW;
-    // every tile requested before the list exists is a prompt tile
-    if (late_list) fetch_prompt(st, ti);
-    // Q tile to LDS and this thread's parent row packed: both were requested
-    // before the tile above, so waiting for them leaves the tile in flight
+    int ti = wave;                                     // static first tile (not for the builder)
+    if (tid == 0) {
+        s_next_tile = has_resp ? NW - 1 : NW;
+        s_list.ready = 0;
+    }
+    const bool early = !is_builder && ti < n_ptiles;   // the first tile needs nothing but addresses
+    if (early) fetch_prompt(st, ti);
+    // Q tile to LDS: requested before the tile above, so waiting for it leaves
+    // the tile in flight
 #pragma unroll
     for (int c = 0; c < QCH; ++c) {
         const int i = tid + c * NT;
         if (i < kQueryTile * CPR)
             *reinterpret_cast<u32x4_t*>(s_q + (i / CPR) * ROWB + ((i % CPR) << 4)) = qw[c];
     }
-    if (has_row) own_map = pack_parent_row(prow, p.W);
-    __syncthreads();                                   // Q tile and tile counter visible
+    __syncthreads();                                   // Q tile, tile counter, list flag visible
     SEGKV_STAMP(1);
-    bool list_pending = late_list;                     // uniform over the work-group
-    if (!late_list) {
-        resolve_list();
+    if (is_builder) {
+        build_response_list_wave(s_list, p.parent, (g == 0 && qb == 0) ? p.anc_out : nullptr, p.B,
+                                 p.W, p.T, b, s0, s1, lrows, lane);
+        need_list();
+        SEGKV_STAMP(2);
+        ti = claim_tile();
+    }
+    if (!early) {
+        if (ti >= n_ptiles) need_list();
         fetch(st, ti);
     }
     SEGKV_PHASE_BEGIN;
     while (ti < n_tiles) {
         stage_to_lds(st);
         const int nxt = claim_tile();
-        fetch(st, nxt);                                // while pending: nxt < 2*NW, a prompt tile
+        if (nxt >= n_ptiles) need_list();
+        fetch(st, nxt);
         SEGKV_PHASE(0);
         process(ti);
         ti = nxt;
-        if (list_pending) {                            // every wave: once, after its first tile
-            resolve_list();
-            list_pending = false;
-        }
     }
     SEGKV_PHASE_DUMP;
 
