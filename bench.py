@@ -59,11 +59,26 @@ class DeviceSet:
         def rnd(*shape):
             return torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).half()
 
+        self.dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+        # V buffers are placed at the library's recommended byte offset from a
+        # 1 KB boundary (K buffers sit on one): see segkv_value_stagger_bytes
+        stagger = segkv.value_stagger_bytes(self.dims)
+
+        def staggered(t):
+            if not stagger:
+                return t
+            big = torch.empty(t.numel() + 512, dtype=torch.float16, device=dev)
+            assert big.data_ptr() % 1024 == 0
+            v = big[stagger // 2: stagger // 2 + t.numel()].view_as(t)
+            v.copy_(t)
+            return v
+
         self.q = rnd(wl.N, wl.Hq, wl.D)
         self.pk = rnd(wl.B, wl.Lp, wl.Hkv, wl.D)
-        self.pv = rnd(wl.B, wl.Lp, wl.Hkv, wl.D)
+        self.pv = staggered(rnd(wl.B, wl.Lp, wl.Hkv, wl.D))
         self.rk = torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16, device=dev)
-        self.rv = torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16, device=dev)
+        self.rv = staggered(torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16,
+                                       device=dev))
         if wl.T > 1:
             self.rk[: wl.T - 1] = rnd(wl.T - 1, wl.N, wl.Hkv, wl.D)
             self.rv[: wl.T - 1] = rnd(wl.T - 1, wl.N, wl.Hkv, wl.D)
@@ -72,7 +87,6 @@ class DeviceSet:
         self.parent = torch.from_numpy(parent_np).to(dev)
         self.slopes = None if slopes_np is None else torch.from_numpy(slopes_np).to(dev)
         self.out = torch.empty(wl.N, wl.Hq, wl.D, dtype=torch.float16, device=dev)
-        self.dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
         nb = segkv.workspace_bytes(self.dims)
         self.ws = torch.empty(max(nb, 16) // 4, dtype=torch.float32, device=dev) if nb else None
         self.call = segkv.prepare_sdpa_decode(self.out, self.q, self.pk, self.pv, self.rk, self.rv,

@@ -24,7 +24,7 @@ SEGKV_HIP_ERROR = -5
 EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_status_string", "segkv_stream_read_probe", "segkv_cache_token_bytes",
            "segkv_cache_standard_bytes", "segkv_cache_segment_bytes", "segkv_response_capacity",
-           "segkv_grow_response", "segkv_sdpa_prefill")
+           "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes")
 
 
 class SegkvDims(ctypes.Structure):
@@ -61,6 +61,8 @@ def load_library():
                                       ctypes.c_float, dp, vp]
     lib.segkv_workspace_bytes.restype = sz
     lib.segkv_workspace_bytes.argtypes = [dp]
+    lib.segkv_value_stagger_bytes.restype = sz
+    lib.segkv_value_stagger_bytes.argtypes = [dp]
     lib.segkv_status_string.restype = ctypes.c_char_p
     lib.segkv_status_string.argtypes = [ctypes.c_int]
     lib.segkv_stream_read_probe.restype = ctypes.c_int
@@ -106,6 +108,10 @@ def _stream_handle(stream) -> Optional[int]:
 
 def workspace_bytes(dims: SegkvDims) -> int:
     return int(load_library().segkv_workspace_bytes(ctypes.byref(dims)))
+
+
+def value_stagger_bytes(dims: SegkvDims) -> int:
+    return int(load_library().segkv_value_stagger_bytes(ctypes.byref(dims)))
 
 
 def append_kv(resp_k, resp_v, k_new, v_new, t: int, dims: SegkvDims, stream=None) -> None:
@@ -177,7 +183,7 @@ def grow_response(new_k, new_v, old_k, old_v, dims: SegkvDims, stream=None) -> N
                                             int(new_k.shape[0]), ctypes.byref(dims),
                                             _stream_handle(stream))
     if rc != SEGKV_OK:
-        raise SegkvError(rc, "segkv_grow_response", "segkv_sdpa_prefill")
+        raise SegkvError(rc, "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes")
 
 
 def stream_read_probe(src, sink, stream=None) -> None:

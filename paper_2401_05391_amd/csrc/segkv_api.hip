@@ -151,6 +151,13 @@ size_t segkv_workspace_bytes(const segkv_dims* d)
     return pl.ws_ml_bytes + pl.ws_acc_bytes;
 }
 
+size_t segkv_value_stagger_bytes(const segkv_dims* d)
+{
+    if (!dims_ok(d) || !dims_supported(d)) return 0;
+    // only the per-head column streams of the matrix-core kernel gain from it
+    return (make_plan(d).mfma && d->D * 2 == 256) ? 256 : 0;
+}
+
 int segkv_append_kv(void* resp_k, void* resp_v, const void* k_new, const void* v_new, int32_t t,
                     const segkv_dims* d, void* stream)
 {
