@@ -42,16 +42,20 @@ bool dims_supported(const segkv_dims* d)
     return (d->D == 64 || d->D == 128 || d->D == 256) && d->beam <= 8;
 }
 
-// Which kernel: the matrix-core path when more than 4 queries share each K/V
-// row (beams and/or grouped query heads), the vector-ALU path (which takes up
-// to 4 queries per work-group and reads 1 KB-contiguous pieces across adjacent
-// heads) otherwise.  SEGKV_PATH=alu|mfma overrides (for A/B measurements).
-bool want_mfma(int nq)
+// Which kernel.  The matrix-core kernel whenever several queries share each K/V
+// row (beams and/or grouped query heads): measured faster than the vector-ALU
+// kernel from 2 queries up at every batch size.  With a single query per row
+// (greedy decode without grouping) it still wins once there are enough
+// (request, KV head) units to keep every CU supplied with whole units (>= 1024:
+// 82% against 80% of peak on the Llama2-7B shape); below that the vector-ALU
+// kernel's finer work items fill the device better.  SEGKV_PATH=alu|mfma
+// overrides (A/B measurements and tests).
+bool want_mfma(int nq, long kv_units)
 {
     const char* s = std::getenv("SEGKV_PATH");
     if (s && s[0] == 'a') return false;
     if (s && s[0] == 'm') return true;
-    return nq > 4;
+    return nq >= 2 || kv_units >= 1024;
 }
 
 // How the keys of one (request, KV head) unit are cut into work-groups.
@@ -62,10 +66,12 @@ Plan make_plan(const segkv_dims* d)
     Plan pl{};
     pl.G = d->Hq / d->Hkv;
     pl.nq = d->beam * pl.G;
-    pl.mfma = want_mfma(pl.nq) ? 1 : 0;
+    pl.mfma = want_mfma(pl.nq, (long)d->B * d->Hkv) ? 1 : 0;
     int target_groups, min_pchunk;
     if (pl.mfma) {
-        pl.QB = 32;
+        // query slots per work-group: the 16-slot shape when it holds all queries
+        // of a unit, and always at D = 256 (accumulator registers)
+        pl.QB = (pl.nq <= 16 || d->D == 256) ? 16 : 32;
         pl.HP = 1;
         target_groups = env_int("SEGKV_TARGET_GROUPS", 256);
         min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * (pl.nq < 32 ? pl.nq : 32));
@@ -225,7 +231,7 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
 #endif
 
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, d->D, pl.grid, st)
+    hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, d->D, pl.QB, pl.grid, st)
                            : segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.HP, pl.grid, st);
     if (e != hipSuccess) return SEGKV_HIP_ERROR;
     if (pl.n_chunks > 1) {

@@ -48,14 +48,12 @@ struct PrefillParams {
 
 constexpr int kMaxStepsPerChunk = 256;   // response steps one work-group can resolve
 constexpr int kMaxListEntries = 1024;    // (step, slot) rows of one chunk: steps * beam <= this
-constexpr int kMfmaWaves64 = 8;           // waves per work-group of the MFMA kernel, by head dim
-constexpr int kMfmaWaves128 = 8;
-constexpr int kMfmaWaves256 = 4;
 constexpr int kProbeGroups = 4096;       // work-groups (and sink words) of the read probe
 
 hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, int HP, unsigned grid,
                               hipStream_t st);
-hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, unsigned grid, hipStream_t st);
+hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, unsigned grid,
+                                   hipStream_t st);
 hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st);
 hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_acc, int NQ, int D,
                              int n_chunks, hipStream_t st);

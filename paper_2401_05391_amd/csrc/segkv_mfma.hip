@@ -3,11 +3,13 @@
 //
 // Used when several queries share every K/V row of a unit (request b, KV head
 // g): the W beams and, under grouped-query attention, the G query heads of the
-// group.  Up to 32 such queries form the N dimension of 32x32x16 fp16 MFMAs, a
-// tile of 32 keys forms M:
+// group.  The queries are the N dimension of the MFMAs, a tile of keys is M:
 //     S^T[key][query]  = K[key][:]   . Q^T[:][query]       (contraction over D)
 //     O^T[d][query]   += V^T[d][key] . P^T[key][query]     (contraction over keys)
 // so that each K/V row is read from HBM once and reused by all queries.
+// Two shapes: QT = 32 query slots on 32x32x16 MFMAs (beams x grouped heads), and
+// QT = 16 slots on 16x16x32 / 16x16x16 MFMAs (beam search without grouping: few
+// queries, half the accumulator registers, head dimension up to 256).
 //
 // Each wave streams its own key tiles, with no work-group barrier in the loop:
 //   global (coalesced 128-bit, non-temporal) -> registers -> wave-private LDS
@@ -62,28 +64,54 @@
 
 namespace segkv {
 
-template <int D, int NW, int DEPTH>
+// Tile geometry of the decode kernel for head dimension D and QT query slots.
+// A wave's tile is 16 KB of K plus V rows: 32 keys, or 16 keys at D = 256.
+template <int D, int QT>
+struct DecodeGeometry {
+    static constexpr int KT = (D == 256) ? 16 : 32;   // keys per tile
+    static constexpr int CPR = D / 8;                 // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;              // rows per staging load instruction
+    static constexpr int NLD = KT / RPI;              // staging loads per operand per tile
+    // Row pitch 2D+16 bytes = 16 mod 256: the 16 (or 32) consecutive rows that read
+    // the same 16-byte column as MFMA operands fall into different bank groups.
+    static constexpr int ROWB = D * 2 + 16;
+    static constexpr int TILEB = KT * ROWB;           // bytes of a K (or V) tile
+    static constexpr int MROW = D + 4;                // floats per query row in the merge layout
+    static constexpr int MERGEB = QT * MROW * 4;
+    static constexpr int REGIONB = (2 * TILEB > MERGEB) ? 2 * TILEB : MERGEB;   // per wave
+    static_assert(QT == 32 || QT == 16, "query slots per work-group");
+    static_assert(QT == 16 || KT == 32, "the 32-slot shape multiplies 32-key tiles");
+};
+
+template <int D, int NW, int DEPTH, int QT>
 __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 {
-    using Geo = MfmaGeometry<D>;
-    constexpr int CPR = Geo::CPR, RPI = Geo::RPI, NLD = Geo::NLD, NKS = Geo::NKS, NDB = Geo::NDB;
-    constexpr int ROWB = Geo::ROWB, VROWB = Geo::VROWB, TILEB = Geo::TILEB, MROW = Geo::MROW;
+    using Geo = DecodeGeometry<D, QT>;
+    constexpr int KT = Geo::KT, CPR = Geo::CPR, RPI = Geo::RPI, NLD = Geo::NLD;
+    constexpr int ROWB = Geo::ROWB, VROWB = Geo::ROWB, TILEB = Geo::TILEB, MROW = Geo::MROW;
     constexpr int REGIONB = Geo::REGIONB;
     constexpr int NT = NW * 64;
-    static_assert(NT >= kListThreads, "the response list needs one thread per step");
+    constexpr bool WIDE = (QT == 32);
+    // accumulator registers per lane: O^T is D x QT fp32 over 64 lanes
+    constexpr int NOB = WIDE ? D / 32 : D / 16;        // blocks of the PV product
+    constexpr int OBR = WIDE ? 16 : 4;                 // registers per block
+    constexpr int NSR = WIDE ? 16 : (KT / 16) * 4;     // S^T registers per lane and tile
 
     __shared__ __align__(16) unsigned char s_region[NW * REGIONB];
-    __shared__ __align__(16) unsigned char s_q[kQueryTile * ROWB];   // Q^T operand, shared by the waves
+    __shared__ __align__(16) unsigned char s_q[QT * ROWB];   // Q^T operand, shared by the waves
     __shared__ ResponseListSmem s_list;
-    __shared__ float s_ml[NW][kQueryTile][2];
+    __shared__ float s_ml[NW][QT][2];
     __shared__ int s_next_tile;                        // next unclaimed tile of the stream
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: tile indices stay uniform
     SEGKV_STAMP(0);
-    const int n = lane & 31;        // query slot (MFMA column) / key row (MFMA A row) / d within block
-    const int h = lane >> 5;        // lane half: which 8 of the 16 contraction slots
+    // MFMA lane roles.  32-slot shape: lane = n + 32 h (n: query column / key row /
+    // d within a block, h: which 8 of the 16 contraction slots).  16-slot shape:
+    // lane = n + 16 h (h = 0..3: which quarter of the contraction slots).
+    const int n = WIDE ? (lane & 31) : (lane & 15);
+    const int h = WIDE ? (lane >> 5) : (lane >> 4);
     const int srow = lane / CPR;    // staging: row within a load instruction
     const int schunk = lane % CPR;  // staging: 16-byte chunk of the row
 
@@ -117,7 +145,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 
     // ---- queries of this block: staged once into LDS in the same padded row
     // layout as the key tiles; every wave reads its QK^T B operand from there ----
-    const int lq = qb * kQueryTile + n;
+    const int lq = qb * QT + n;
     const bool q_valid = lq < p.nq;
     const int lqc = q_valid ? lq : (p.nq - 1);
     const int qbeam = lqc / p.G;
@@ -128,16 +156,16 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     // chunks this thread stages, its row of the parent table, then (below) the
     // wave's first key tile.  They are consumed in the same order, so each wait
     // leaves the younger requests in flight.
-    constexpr int QCH = (kQueryTile * CPR + NT - 1) / NT;
+    constexpr int QCH = (QT * CPR + NT - 1) / NT;
     u32x4_t qw[QCH];
 #pragma unroll
     for (int c = 0; c < QCH; ++c) {
         const int i = tid + c * NT;
         const int qn = i / CPR;
         const int ch = i % CPR;
-        const int lqn = qb * kQueryTile + qn;
+        const int lqn = qb * QT + qn;
         qw[c] = u32x4_t{0u, 0u, 0u, 0u};               // unused query slots multiply as zeros
-        if (i < kQueryTile * CPR && lqn < p.nq) {
+        if (i < QT * CPR && lqn < p.nq) {
             const size_t row = (size_t)(b * p.W + lqn / p.G) * p.Hq + g * p.G + (lqn % p.G);
             qw[c] = load16(p.q + row * D + ch * 8);
         }
@@ -170,12 +198,13 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     SEGKV_PHASE_DECL;
     // ---- running state: reference max and partial sum per lane, O^T accumulators ----
     float m_ref = kEmptyMax;
-    float l_part = 0.0f;            // sum of p over this lane's 16 keys of every tile
-    float16_t o_acc[NDB];
+    float l_part = 0.0f;            // sum of p over this lane's keys of every tile
+    typedef float acc_t __attribute__((ext_vector_type(OBR)));
+    acc_t o_acc[NOB];
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
+    for (int ob = 0; ob < NOB; ++ob)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.0f;
+        for (int r = 0; r < OBR; ++r) o_acc[ob][r] = 0.0f;
 
     struct Staged {
         u32x4_t k[NLD];
@@ -192,42 +221,67 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         }
     };
 
-    // One tile of 32 keys.  `mode` (uniform) selects how S^T becomes base-2 logits:
+    // One tile of KT keys.  `mode` (uniform) selects how S^T becomes base-2 logits:
     // 0 full prompt tile without positional bias, 1 prompt tile with masking of
     // the tail and ALiBi, 2 response tile (per-row beam masks and positions).
+    // Register r of S^T holds, for this lane's query, the key at tile row
+    //   32-slot shape: 8 (r / 4) + 4 h + (r % 4)
+    //   16-slot shape: 16 (r / 4) + 4 h + (r % 4)
+    auto key_row = [&](int r) { return (WIDE ? 8 : 16) * (r >> 2) + 4 * h + (r & 3); };
     auto compute_tile = [&](int mode, int base, int total) __attribute__((always_inline)) {
         // S^T = K . Q^T
-        float16_t s;
+        float s[NSR];
+        if constexpr (WIDE) {
+            float16_t acc;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
-        for (int t = 0; t < NKS; ++t) {
-            const int off = n * ROWB + ((2 * t + h) << 4);
-            const half8_t a = *reinterpret_cast<const half8_t*>(k_tile + off);
-            const half8_t bq = *reinterpret_cast<const half8_t*>(s_q + off);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq, s, 0, 0, 0);
+            for (int t = 0; t < D / 16; ++t) {
+                const int off = n * ROWB + ((2 * t + h) << 4);
+                const half8_t a = *reinterpret_cast<const half8_t*>(k_tile + off);
+                const half8_t bq = *reinterpret_cast<const half8_t*>(s_q + off);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = acc[r];
+        } else {
+            // 16 keys x 16 queries per MFMA, 32 head-dim elements per step
+#pragma unroll
+            for (int kb = 0; kb < KT / 16; ++kb) {
+                float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int t = 0; t < D / 32; ++t) {
+                    const int col = (4 * t + h) << 4;
+                    const half8_t a =
+                        *reinterpret_cast<const half8_t*>(k_tile + (16 * kb + n) * ROWB + col);
+                    const half8_t bq = *reinterpret_cast<const half8_t*>(s_q + n * ROWB + col);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq, acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) s[4 * kb + r] = acc[r];
+            }
         }
         SEGKV_PHASE(1);
         // logits, tile maximum for this lane's query
         float m_tile = -INFINITY;
         if (mode == 0) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < NSR; ++r) {
                 s[r] *= p.scale2;
                 m_tile = fmaxf(m_tile, s[r]);
             }
         } else if (mode == 1) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kpos = base + 8 * (r >> 2) + 4 * h + (r & 3);
+            for (int r = 0; r < NSR; ++r) {
+                const int kpos = base + key_row(r);
                 const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
                 s[r] = kpos < k1 ? z : -INFINITY;
                 m_tile = fmaxf(m_tile, s[r]);
             }
         } else {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int e = base + 8 * (r >> 2) + 4 * h + (r & 3);
+            for (int r = 0; r < NSR; ++r) {
+                const int e = base + key_row(r);
                 const uint32_t ent = s_list.ent[min(e, total - 1)];
                 const int kpos = p.Lp + s0 + (int)(ent >> 16);
                 const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
@@ -236,7 +290,13 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
                 m_tile = fmaxf(m_tile, s[r]);
             }
         }
-        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+        // the lanes that share this lane's query
+        if constexpr (WIDE) {
+            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+        } else {
+            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16));
+            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+        }
         // move the reference maximum only when a tile exceeds it by the slack
         if (__any(m_tile > m_ref + kRescaleSlack)) {
             const float m_new = fmaxf(m_ref, m_tile);
@@ -244,41 +304,58 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
             m_ref = m_new;
             l_part *= corr;
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
+            for (int ob = 0; ob < NOB; ++ob)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o_acc[db][r] *= corr;
+                for (int r = 0; r < OBR; ++r) o_acc[ob][r] *= corr;
         }
         // P = 2^(z - m_ref), fp16 for the PV product
-        half8_t pb[2];
+        _Float16 ph[NSR];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
+        for (int r = 0; r < NSR; ++r) {
             const float pr = fast_exp2(s[r] - m_ref);
             l_part += pr;
-            pb[r >> 3][r & 7] = (_Float16)pr;
+            ph[r] = (_Float16)pr;
         }
         SEGKV_PHASE(2);
-        // O^T += V^T . P^T.  The A operand wants, per lane, 8 keys of one head-dim
-        // column; the V tile is row-major [key][d].  ds_read_b64_tr_b16 does the
-        // transpose on the way out of LDS: a 16-lane group reads 4 rows x 16
-        // columns (lane i supplies row i/4, columns 4*(i%4)..+3) and lane i
-        // receives column i of all 4 rows.  Two such reads give the 8 keys
-        // 16u + 8r + 4h + {0..3}, r = 0, 1, matching the keys of P's registers.
-        {
+        // O^T += V^T . P^T.  The A operand wants, per lane, several keys of one
+        // head-dim column; the V tile is row-major [key][d].  ds_read_b64_tr_b16
+        // does the transpose on the way out of LDS: a 16-lane group reads 4 rows x
+        // 16 columns (lane i supplies row i/4, columns 4*(i%4)..+3) and lane i
+        // receives column i of all 4 rows.
+        const int li = lane & 15;
+        if constexpr (WIDE) {
+            // two reads give the 8 keys 16u + 8r + 4h + {0..3}, r = 0, 1, the keys
+            // of S^T registers 8u .. 8u+7
             const int grp = lane >> 4;                 // 16-lane group: d half (grp&1), key half h
-            const int li = lane & 15;
             const int tr_base = (4 * h + (li >> 2)) * VROWB + ((16 * (grp & 1) + 4 * (li & 3)) << 1);
 #pragma unroll
-            for (int db = 0; db < NDB; ++db) {
+            for (int ob = 0; ob < NOB; ++ob) {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
-                    const int off = tr_base + (16 * u) * VROWB + db * 64;
+                    const int off = tr_base + (16 * u) * VROWB + ob * 64;
                     const half4_t lo = lds_read_tr16(v_tile + off);
                     const half4_t hi = lds_read_tr16(v_tile + off + 8 * VROWB);
                     const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                    o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
+                    const half8_t pb = {ph[8 * u + 0], ph[8 * u + 1], ph[8 * u + 2], ph[8 * u + 3],
+                                        ph[8 * u + 4], ph[8 * u + 5], ph[8 * u + 6], ph[8 * u + 7]};
+                    o_acc[ob] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb, o_acc[ob], 0, 0, 0);
                 }
                 // keep the operand reads of later blocks from piling up in registers
-                if (NDB > 4) __builtin_amdgcn_sched_barrier(0);
+                if (NOB > 4) __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+            // 16 head-dim columns x 16 queries per MFMA, contraction over the 16 keys
+            // of block kb: one read gives keys 16 kb + 4 h + {0..3}, the keys of S^T
+            // registers 4 kb .. 4 kb + 3
+            const int tr_base = (4 * h + (li >> 2)) * VROWB + ((4 * (li & 3)) << 1);
+#pragma unroll
+            for (int kb = 0; kb < KT / 16; ++kb) {
+                const half4_t pb = {ph[4 * kb + 0], ph[4 * kb + 1], ph[4 * kb + 2], ph[4 * kb + 3]};
+#pragma unroll
+                for (int ob = 0; ob < NOB; ++ob) {
+                    const half4_t a = lds_read_tr16(v_tile + tr_base + (16 * kb) * VROWB + ob * 32);
+                    o_acc[ob] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, pb, o_acc[ob], 0, 0, 0);
+                }
             }
         }
         SEGKV_PHASE(3);
@@ -292,15 +369,15 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     // never skipped: past the end of the stream it is pointed at one row that is
     // already cached, so that the code is free of conditional loads and every
     // wait covers exactly the tile it needs. ----
-    const int n_ptiles = (k1 > k0) ? (k1 - k0 + kKeyTile - 1) / kKeyTile : 0;
+    const int n_ptiles = (k1 > k0) ? (k1 - k0 + KT - 1) / KT : 0;
     const _Float16* const dummy = p.q + (size_t)b * p.W * p.Hq * D + schunk * 8;
     // Prompt tiles are addressed as (scalar tile base) + (32-bit lane offset):
     // the lane offsets are the same for every full tile, so no per-load 64-bit
     // address has to be kept in registers.
     const uint32_t row_stride = (uint32_t)p.Hkv * D;   // elements between consecutive keys
     auto fetch_prompt = [&](Staged& st, int ti) __attribute__((always_inline)) {
-        const int base = k0 + ti * kKeyTile;
-        const int lim = min(kKeyTile - 1, k1 - 1 - base);          // last valid row of the tile
+        const int base = k0 + ti * KT;
+        const int lim = min(KT - 1, k1 - 1 - base);          // last valid row of the tile
         const size_t tile_off = (((size_t)b * p.Lp + base) * p.Hkv + g) * D;
         const _Float16* const kb = p.prompt_k + tile_off;
         const _Float16* const vb = p.prompt_v + tile_off;
@@ -330,7 +407,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     auto need_list = [&]() {
         if (!list_known) {
             total = wait_response_list(s_list);
-            n_tiles = n_ptiles + (total + kKeyTile - 1) / kKeyTile;
+            n_tiles = n_ptiles + (total + KT - 1) / KT;
             list_known = true;
         }
     };
@@ -341,7 +418,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     };
 
     auto fetch_response = [&](Staged& st, int ti) __attribute__((always_inline)) {
-        const int base = ti * kKeyTile;
+        const int base = ti * KT;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int e = min(base + RPI * i + srow, total - 1);
@@ -366,11 +443,11 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     };
     auto process = [&](int ti) __attribute__((always_inline)) {
         if (ti < n_ptiles) {
-            const int base = k0 + ti * kKeyTile;
-            const bool plain = (p.slopes == nullptr) && (base + kKeyTile <= k1);
+            const int base = k0 + ti * KT;
+            const bool plain = (p.slopes == nullptr) && (base + KT <= k1);
             compute_tile(plain ? 0 : 1, base, 0);
         } else {
-            compute_tile(2, (ti - n_ptiles) * kKeyTile, total);
+            compute_tile(2, (ti - n_ptiles) * KT, total);
         }
     };
 
@@ -393,7 +470,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 #pragma unroll
     for (int c = 0; c < QCH; ++c) {
         const int i = tid + c * NT;
-        if (i < kQueryTile * CPR)
+        if (i < QT * CPR)
             *reinterpret_cast<u32x4_t*>(s_q + (i / CPR) * ROWB + ((i % CPR) << 4)) = qw[c];
     }
     if (appends) {
@@ -447,14 +524,17 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     SEGKV_STAMP(4);
     // ---- merge the waves through LDS (each wave reuses its own tile region) ----
     l_part += __shfl_xor(l_part, 32);
+    if constexpr (!WIDE) l_part += __shfl_xor(l_part, 16);
     float* const mrg = reinterpret_cast<float*>(region);
+    // register j of block ob is O^T[d][n] with d = (WIDE ? 32 ob + 8 (j/4) + 4 h : 16 ob + 4 h) + j%4
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
+    for (int ob = 0; ob < NOB; ++ob)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float4_t v4 = {o_acc[db][4 * i + 0], o_acc[db][4 * i + 1], o_acc[db][4 * i + 2],
-                           o_acc[db][4 * i + 3]};
-            *reinterpret_cast<float4_t*>(mrg + n * MROW + 32 * db + 8 * i + 4 * h) = v4;
+        for (int i = 0; i < OBR / 4; ++i) {
+            float4_t v4 = {o_acc[ob][4 * i + 0], o_acc[ob][4 * i + 1], o_acc[ob][4 * i + 2],
+                           o_acc[ob][4 * i + 3]};
+            const int d0 = WIDE ? 32 * ob + 8 * i + 4 * h : 16 * ob + 4 * h;
+            *reinterpret_cast<float4_t*>(mrg + n * MROW + d0) = v4;
         }
     if (h == 0) {
         s_ml[wave][n][0] = m_ref;
@@ -464,7 +544,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     SEGKV_STAMP(5);
 
     const int NQ = N * p.Hq;
-    const int nq_here = min(kQueryTile, p.nq - qb * kQueryTile);
+    const int nq_here = min(QT, p.nq - qb * QT);
     for (int idx = tid; idx < nq_here * (D / 4); idx += NT) {
         const int qn = idx / (D / 4);
         const int d4 = (idx % (D / 4)) * 4;
@@ -481,7 +561,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
                 reinterpret_cast<const float*>(s_region + w * REGIONB) + qn * MROW + d4);
             aa += a * f;
         }
-        const int lqn = qb * kQueryTile + qn;
+        const int lqn = qb * QT + qn;
         const int j = lqn / p.G;
         const int hqn = g * p.G + (lqn % p.G);
         const size_t row = (size_t)(b * p.W + j) * p.Hq + hqn;
@@ -507,25 +587,29 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 // ---------------------------------------------------------------------------
 // Host-side launcher
 // ---------------------------------------------------------------------------
-template <int D, int NW, int DEPTH>
+template <int D, int NW, int DEPTH, int QT>
 static void launch_variant(const SdpaParams& p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, DEPTH>), dim3(grid), dim3(NW * 64), 0, st, p);
+    hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, DEPTH, QT>), dim3(grid), dim3(NW * 64), 0, st,
+                       p);
 }
 
-hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, unsigned grid, hipStream_t st)
+hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, unsigned grid, hipStream_t st)
 {
-    const char* v = std::getenv("SEGKV_MFMA_VARIANT");   // A/B measurements: "<waves><depth>"
-    const int var = v ? std::atoi(v) : 0;
+    if (QT != 16 && QT != 32) return hipErrorInvalidValue;
     switch (D) {
-        case 64:  launch_variant<64, kMfmaWaves64, 1>(p, grid, st); break;
-        case 128:
-            if (var == 42)      launch_variant<128, 4, 2>(p, grid, st);
-            else if (var == 41) launch_variant<128, 4, 1>(p, grid, st);
-            else if (var == 82) launch_variant<128, 8, 2>(p, grid, st);
-            else                launch_variant<128, kMfmaWaves128, 1>(p, grid, st);
+        case 64:
+            if (QT == 32) launch_variant<64, 8, 1, 32>(p, grid, st);
+            else          launch_variant<64, 8, 1, 16>(p, grid, st);
             break;
-        case 256: launch_variant<256, kMfmaWaves256, 1>(p, grid, st); break;
+        case 128:
+            if (QT == 32) launch_variant<128, 8, 1, 32>(p, grid, st);
+            else          launch_variant<128, 8, 1, 16>(p, grid, st);
+            break;
+        case 256:
+            if (QT == 32) return hipErrorInvalidValue;   // accumulators would not fit: planner uses 16
+            launch_variant<256, 8, 1, 16>(p, grid, st);
+            break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -57,6 +57,11 @@ SMALL = [
     Workload("one_key", B=1, W=1, Hq=1, Hkv=1, D=64, Lp=0, T=1, parents="identity", seed=112),
     Workload("full_cap", B=1, W=4, Hq=2, Hkv=2, D=128, Lp=17, T=32, seed=113),
     Workload("long_resp", B=1, W=4, Hq=2, Hkv=1, D=64, Lp=10, T=256, seed=114),
+    # more than 16 queries per KV head: two 16-slot query blocks at D = 256, the
+    # 32-slot shape at D = 64
+    Workload("d256_gqa8", B=1, W=4, Hq=16, Hkv=2, D=256, Lp=83, T=21, seed=115),
+    Workload("d64_gqa8", B=2, W=4, Hq=8, Hkv=1, D=64, Lp=99, T=27, alibi=True, seed=116),
+    Workload("d128_w1_gqa4", B=3, W=1, Hq=8, Hkv=2, D=128, Lp=140, T=20, parents="identity", seed=117),
 ]
 
 
