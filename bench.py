@@ -276,6 +276,10 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=20.0,
                     help="CPU-core-seconds to spend on the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fig6-sweep", action="store_true",
+                    help="instead of the headline workload, time the paper's Figure 6 experiment "
+                         "(Llama2-13B attention shape, beam 4, 1024/128 tokens, batch size 1..64) and "
+                         "print its table as one JSON line")
     ap.add_argument("--calibrate-counters", action="store_true",
                     help="also launch a plain copy of known size (segkv_append_kv, 2 x 128 MiB read and "
                          "written) and a plain read of known size (segkv_stream_read_probe, 1 GiB), "
@@ -294,6 +298,28 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     segkv.load_library()
+
+    if a.fig6_sweep:
+        from paper_2401_05391_amd.workloads import FIG6_BATCH_SIZES, fig6_workload
+        rows = []
+        for bs in FIG6_BATCH_SIZES:
+            r = time_workload(fig6_workload(bs), a.steps, a.warmup, segkv, torch, False, 0)
+            rows.append({"batch_size": bs, "us_per_layer_step": r["us_per_layer_step"],
+                         "device_us_mean": r["device_us"]["mean"], "bytes_unique": r["bytes_unique"],
+                         "bytes_nominal": r["bytes_nominal"], "gbs_unique": r["gbs_unique"],
+                         "gbs_nominal": r["gbs_nominal"], "frac_of_peak": r["roofline"]["frac"],
+                         "stream_read_probe_gbs": r["stream_read_probe_gbs"]})
+        last = rows[-1]
+        print(json.dumps({
+            "metric": "fused segment-KV decode SDPA: achieved HBM GB/s, Figure 6 batch-size sweep",
+            "value": last["gbs_unique"], "unit": "GB/s", "n_gpus": 1, "steps": a.steps,
+            "warmup": a.warmup, "ms_per_step": last["us_per_layer_step"] * 1e-3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+            "data": "synthetic",
+            "config": {"workload": "fig6_llama2_13b_sweep", "beam": 4, "Hq": 40, "Hkv": 40, "D": 128,
+                       "Lp": 1024, "T": 128, "value_is_batch_size": last["batch_size"]},
+            "sweep": rows}), flush=True)
+        return
 
     wl = CONFIGS[a.workload]
     main_res = time_workload(wl, a.steps, a.warmup, segkv, torch, not a.no_cpu_baseline, a.cpu_seconds)

@@ -66,6 +66,17 @@ CONFIGS: Dict[str, Workload] = {
 }
 
 
+# The paper's own kernel experiment (Section 4.1, Figure 6): the attention
+# shape of Llama2-13B (40 heads of 128), beam width 4, 1024 prompt tokens, 128
+# response steps, batch size swept from 1 to 64.
+FIG6_BATCH_SIZES = (1, 2, 4, 8, 16, 32, 64)
+
+
+def fig6_workload(batch_size: int) -> Workload:
+    return Workload(f"llama2_13b_bs{batch_size}", B=batch_size, W=4, Hq=40, Hkv=40, D=128,
+                    Lp=1024, T=128, seed=13)
+
+
 def alibi_slopes(Hq: int) -> np.ndarray:
     """Per-head slopes 2^(-8 h / Hq), h = 1..Hq (fp32).  The formula lives only
     here; both the oracle and the GPU library take the array as an input."""

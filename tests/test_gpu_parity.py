@@ -222,3 +222,15 @@ def test_full_size_configs(name):
     print(f"[parity] {name}: max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}", flush=True)
     assert same_bits(res["resp_k"][wl.T - 1], x["k_new"])
     assert same_bits(res["resp_v"][wl.T - 1], x["v_new"])
+
+
+@pytest.mark.parametrize("bs", [1, 4])
+def test_fig6_llama2_13b_shape(bs):
+    # the paper's own kernel experiment (Section 4.1, Figure 6) at two of its batch
+    # sizes: batch 1 exercises the split-KV plan, batch 4 more units than one round
+    from paper_2401_05391_amd.workloads import fig6_workload
+    wl = fig6_workload(bs)
+    x = make_inputs(wl)
+    res = run_gpu(wl, x, fused=True)
+    ref_out, ref_anc, ref_rk, ref_rv = oracle_reference(wl, x)
+    _check(wl, x, res, ref_out, ref_anc, ref_rk, ref_rv, wl.name)
