@@ -69,6 +69,33 @@ int segkv_append_kv(void* resp_k, void* resp_v,
                     int32_t t, const segkv_dims* d, void* stream);
 
 /*
+ * Producer step of a decode step (Section 3.1: RoPE follows the QKV projection
+ * and is fused to a single kernel; the step's Key_t / Value_t are kept in their
+ * row of the response buffers).  One launch that
+ *   - rotates q [B*beam, Hq, D] IN PLACE,
+ *   - writes the rotated k_new [B*beam, Hkv, D] to row t of resp_k,
+ *   - copies v_new [B*beam, Hkv, D] to row t of resp_v,
+ * after which segkv_sdpa_decode is called with T = t + 1 and k_new = v_new = NULL.
+ * Rotary embedding as published (RoFormer): theta_i = rope_base^(-2i/rotary_dim),
+ * i < rotary_dim/2; the pair (a, b) at position pos becomes
+ * (a cos(pos theta_i) - b sin(pos theta_i), b cos(pos theta_i) + a sin(pos theta_i)).
+ * The pair is elements (i, i + rotary_dim/2) of a head vector when interleaved
+ * == 0 (Llama2) and (2i, 2i+1) otherwise (GPT-J); elements >= rotary_dim pass
+ * through.  rotary_dim <= min(D, 256), a multiple of 16 (of 8 when interleaved);
+ * 0 makes this a plain append.
+ *   positions   NULL: every row sits at position d->Lp + t (prompt token i at i,
+ *               response step s at Lp + s, as for the ALiBi bias); else [B] int32
+ *               device array with the position of each request's current token.
+ * Angles are evaluated in double precision, the rotation in fp32, results are
+ * rounded to fp16 (round to nearest even).  Uses d->B, beam, Hq, Hkv, D, Lp,
+ * Tcap; 0 <= t < Tcap.
+ */
+int segkv_rope_append(void* q, const void* k_new, const void* v_new,
+                      void* resp_k, void* resp_v, const int32_t* positions,
+                      int32_t t, float rope_base, int32_t rotary_dim, int32_t interleaved,
+                      const segkv_dims* d, void* stream);
+
+/*
  * Fused decode-step attention (Section 3.3).
  *   out           [B*beam, Hq, D] fp16, written.
  *   q             [B*beam, Hq, D] fp16.

@@ -24,7 +24,8 @@ SEGKV_HIP_ERROR = -5
 EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_status_string", "segkv_stream_read_probe", "segkv_cache_token_bytes",
            "segkv_cache_standard_bytes", "segkv_cache_segment_bytes", "segkv_response_capacity",
-           "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes")
+           "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
+           "segkv_rope_append")
 
 
 class SegkvDims(ctypes.Structure):
@@ -78,6 +79,8 @@ def load_library():
     lib.segkv_response_capacity.argtypes = [i32]
     lib.segkv_sdpa_prefill.restype = ctypes.c_int
     lib.segkv_sdpa_prefill.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, dp, vp]
+    lib.segkv_rope_append.restype = ctypes.c_int
+    lib.segkv_rope_append.argtypes = [vp, vp, vp, vp, vp, vp, i32, ctypes.c_float, i32, i32, dp, vp]
     lib.segkv_grow_response.restype = ctypes.c_int
     lib.segkv_grow_response.argtypes = [vp, vp, vp, vp, i32, dp, vp]
     _lib = lib
@@ -119,6 +122,16 @@ def append_kv(resp_k, resp_v, k_new, v_new, t: int, dims: SegkvDims, stream=None
                                         int(t), ctypes.byref(dims), _stream_handle(stream))
     if rc != SEGKV_OK:
         raise SegkvError(rc, "segkv_append_kv")
+
+
+def rope_append(q, k_new, v_new, resp_k, resp_v, t: int, dims: SegkvDims, rope_base: float,
+                rotary_dim: int, interleaved: bool = False, positions=None, stream=None) -> None:
+    rc = load_library().segkv_rope_append(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(resp_k),
+                                          _ptr(resp_v), _ptr(positions), int(t), float(rope_base),
+                                          int(rotary_dim), int(bool(interleaved)),
+                                          ctypes.byref(dims), _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_rope_append")
 
 
 def sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvDims, scale: float,
@@ -183,7 +196,8 @@ def grow_response(new_k, new_v, old_k, old_v, dims: SegkvDims, stream=None) -> N
                                             int(new_k.shape[0]), ctypes.byref(dims),
                                             _stream_handle(stream))
     if rc != SEGKV_OK:
-        raise SegkvError(rc, "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes")
+        raise SegkvError(rc, "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
+           "segkv_rope_append")
 
 
 def stream_read_probe(src, sink, stream=None) -> None:

@@ -2,6 +2,7 @@
 // Declarations and the full contract are in include/segkv.h.
 #include "segkv.h"
 
+#include <cmath>
 #include <cstdlib>
 
 #include "segkv_launch.h"
@@ -240,6 +241,37 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
         if (e != hipSuccess) return SEGKV_HIP_ERROR;
     }
     return SEGKV_OK;
+}
+
+int segkv_rope_append(void* q, const void* k_new, const void* v_new, void* resp_k, void* resp_v,
+                      const int32_t* positions, int32_t t, float rope_base, int32_t rotary_dim,
+                      int32_t interleaved, const segkv_dims* d, void* stream)
+{
+    if (!d || !q || !k_new || !v_new || !resp_k || !resp_v) return SEGKV_INVALID_ARG;
+    if (d->B < 1 || d->beam < 1 || d->Hq < 1 || d->Hkv < 1 || d->D < 1 || d->Lp < 0 || d->Tcap < 1)
+        return SEGKV_INVALID_ARG;
+    if (t < 0 || t >= d->Tcap) return SEGKV_INVALID_ARG;
+    if (!(rope_base > 0.0f) || rotary_dim < 0 || rotary_dim > d->D) return SEGKV_INVALID_ARG;
+    if ((d->D % 8) != 0 || rotary_dim > 256 || (rotary_dim % (interleaved ? 8 : 16)) != 0)
+        return SEGKV_UNSUPPORTED;
+    if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(resp_k) ||
+        misaligned(resp_v) || ((uintptr_t)positions & 3u))
+        return SEGKV_MISALIGNED;
+    const size_t row_elems = (size_t)d->B * d->beam * d->Hkv * d->D;
+    segkv::RopeParams p{};
+    p.q = (_Float16*)q;
+    p.k_new = (const _Float16*)k_new;
+    p.v_new = (const _Float16*)v_new;
+    p.resp_k_row = (_Float16*)resp_k + (size_t)t * row_elems;
+    p.resp_v_row = (_Float16*)resp_v + (size_t)t * row_elems;
+    p.positions = positions;
+    p.pos_default = d->Lp + t;
+    p.W = d->beam; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D;
+    p.R = rotary_dim;
+    p.log2_base = std::log2((double)rope_base);
+    const hipError_t e =
+        segkv::launch_rope_append(p, interleaved ? 1 : 0, d->B * d->beam, (hipStream_t)stream);
+    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
 }
 
 int segkv_sdpa_prefill(void* out, const void* q, const void* k, const void* v,

@@ -46,6 +46,19 @@ struct PrefillParams {
     int B, N0, Hq, Hkv, G;
 };
 
+struct RopeParams {
+    _Float16* q;               // [rows, Hq, D], rotated in place
+    const _Float16* k_new;     // [rows, Hkv, D]
+    const _Float16* v_new;     // [rows, Hkv, D]
+    _Float16* resp_k_row;      // row t of resp_k: [rows, Hkv, D]
+    _Float16* resp_v_row;
+    const int32_t* positions;  // [B] or null
+    int pos_default;           // Lp + t
+    int W, Hq, Hkv, D;
+    int R;                     // rotary dimension
+    double log2_base;
+};
+
 constexpr int kMaxStepsPerChunk = 256;   // response steps one work-group can resolve
 constexpr int kMaxListEntries = 1024;    // (step, slot) rows of one chunk: steps * beam <= this
 constexpr int kProbeGroups = 4096;       // work-groups (and sink words) of the read probe
@@ -59,6 +72,7 @@ hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_
                              int n_chunks, hipStream_t st);
 hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const void* src_v,
                             size_t bytes, hipStream_t st);
+hipError_t launch_rope_append(const RopeParams& p, int interleaved, int rows, hipStream_t st);
 hipError_t launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
 
 }  // namespace segkv
