@@ -233,6 +233,59 @@ def cpu_baseline(wl, x, bytes_unique, budget_s, U):
             "ms_per_step_extrapolated": t / frac * 1e3}
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0     # MI355X published dense fp16 matrix-core peak
+
+# (name, B, N0, Hq, Hkv, D): prompt batches of the benchmark models' attention shapes
+PREFILL_SHAPES = [
+    ("llama2_7b_prefill", 16, 1024, 32, 32, 128),
+    ("llama2_70b_gqa_prefill", 4, 2048, 64, 8, 128),
+    ("gptj6b_prefill", 16, 1024, 16, 16, 256),
+    ("llama2_7b_prefill_4k", 4, 4096, 32, 32, 128),
+]
+
+
+def prefill_bench(steps, warmup, segkv, torch):
+    """Causal prefill attention: 4 * B * Hq * D * N0 (N0 + 1) / 2 flops per call."""
+    dev = torch.device("cuda:0")
+    rows = []
+    for name, B, N0, Hq, Hkv, D in PREFILL_SHAPES:
+        g = torch.Generator(device=dev)
+        g.manual_seed(7)
+        rnd = lambda *s: torch.randn(*s, generator=g, device=dev, dtype=torch.float32).half()
+        q, k, v = rnd(B, N0, Hq, D), rnd(B, N0, Hkv, D), rnd(B, N0, Hkv, D)
+        out = torch.empty_like(q)
+        dims = segkv.make_dims(B, 1, Hq, Hkv, D, N0, 1, 1)
+        for _ in range(warmup):
+            segkv.sdpa_prefill(out, q, k, v, dims, D ** -0.5)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(steps)]
+        t0 = time.perf_counter()
+        for e0, e1 in evs:
+            e0.record()
+            segkv.sdpa_prefill(out, q, k, v, dims, D ** -0.5)
+            e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        dev_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+        flops = 4.0 * B * Hq * D * N0 * (N0 + 1) / 2
+        rows.append({"workload": name, "shape": {"B": B, "N0": N0, "Hq": Hq, "Hkv": Hkv, "D": D},
+                     "ms_per_step": wall_ms, "device_us_mean": dev_ms * 1e3, "flops": flops,
+                     "tflops": flops / (dev_ms * 1e-3) / 1e12,
+                     "tokens_per_s": B * N0 / (wall_ms * 1e-3)})
+        del q, k, v, out
+    head = rows[0]
+    return {"metric": "prefill causal SDPA (segkv_sdpa_prefill): achieved fp16 TFLOP/s",
+            "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+            "config": {"workload": head["workload"], **head["shape"]},
+            "roofline": {"bound": "mfma", "achieved": head["tflops"], "peak": MFMA_F16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": head["tflops"] / MFMA_F16_PEAK_TFLOPS,
+                         "traffic": None},
+            "cpu_baseline": None, "shapes": rows}
+
+
 def run_counter_calibration(segkv, torch):
     """Kernels of known HBM traffic for scaling hardware counters: a copy
     (append of one very wide row: 2 x 128 MiB read, 2 x 128 MiB written) and a
@@ -280,6 +333,10 @@ def main():
                     help="instead of the headline workload, time the paper's Figure 6 experiment "
                          "(Llama2-13B attention shape, beam 4, 1024/128 tokens, batch size 1..64) and "
                          "print its table as one JSON line")
+    ap.add_argument("--prefill", action="store_true",
+                    help="instead of the decode step, time segkv_sdpa_prefill (causal prompt attention, "
+                         "the step that writes the prompt segment) on the shapes of the benchmark "
+                         "models and print one JSON line with an MFMA roofline")
     ap.add_argument("--calibrate-counters", action="store_true",
                     help="also launch a plain copy of known size (segkv_append_kv, 2 x 128 MiB read and "
                          "written) and a plain read of known size (segkv_stream_read_probe, 1 GiB), "
@@ -298,6 +355,10 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     segkv.load_library()
+
+    if a.prefill:
+        print(json.dumps(prefill_bench(a.steps, a.warmup, segkv, torch)), flush=True)
+        return
 
     if a.fig6_sweep:
         from paper_2401_05391_amd.workloads import FIG6_BATCH_SIZES, fig6_workload
