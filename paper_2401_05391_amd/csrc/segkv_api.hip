@@ -94,12 +94,23 @@ Plan make_plan(const segkv_dims* d)
     pl.n_qblocks = ceil_div(pl.nq, pl.QB);
     const long units = (long)d->B * (d->Hkv / pl.HP) * pl.n_qblocks;
 
-    // response steps one work-group may own: one list thread per step, and at
-    // most kMaxListEntries (step, slot) rows
-    int max_steps = segkv::kMaxListEntries / d->beam;
-    if (max_steps > segkv::kMaxStepsPerChunk) max_steps = segkv::kMaxStepsPerChunk;
+    // response steps one work-group may own.  Matrix-core kernel: one wave resolves
+    // them window by window into an LDS list sized by what the tiles leave free
+    // (worst case W distinct rows per step).  Vector-ALU kernel: one list thread
+    // per step, at most kMaxListEntries (step, slot) rows.
+    int max_steps, max_steps_merged;
+    if (pl.mfma) {
+        max_steps_merged = segkv::mfma_list_capacity(d->D, pl.QB) / d->beam;
+        if (max_steps_merged > 65535) max_steps_merged = 65535;
+        max_steps = max_steps_merged < segkv::kMaxStepsPerChunk ? max_steps_merged
+                                                                : segkv::kMaxStepsPerChunk;
+    } else {
+        max_steps = segkv::kMaxListEntries / d->beam;
+        if (max_steps > segkv::kMaxStepsPerChunk) max_steps = segkv::kMaxStepsPerChunk;
+        max_steps_merged = max_steps;
+    }
 
-    if (d->T <= max_steps && units >= target_groups) {
+    if (d->T <= max_steps_merged && units >= target_groups) {
         pl.merged = 1;
         pl.n_chunks = 1;
         pl.n_rchunks = 1;

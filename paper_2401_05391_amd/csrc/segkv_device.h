@@ -58,7 +58,6 @@ struct ResponseListSmem {
     int wave_cnt[kListThreads / 64];
     uint32_t ent[kMaxListEntries];
     int total;
-    int ready;                         // single-wave builder: set (release) once ent/total are final
 };
 
 // One step's parent slots of request b, as loaded (not yet packed), so that a
@@ -210,144 +209,232 @@ __device__ void build_response_list(ResponseListSmem& sm, const int32_t* parent,
 // The same list built by ONE wave, with no work-group barrier: the other waves
 // of the group keep streaming prompt tiles meanwhile and pick the list up
 // through `ready` when they reach their first response tile.
-// Lane i owns the local steps 4i..4i+3 of the chunk (kMaxStepsPerChunk = 256).
+//
+// Beam maps are kept one BYTE per beam here (byte j = slot of beam j), so that a
+// composition is two v_perm_b32 byte permutes.  The chunk's steps are walked in
+// windows of 256 (4 per lane) from the last window to the first -- the slot map
+// of a step is a suffix composition, so it flows backwards -- and each window's
+// entries are placed below the previous window's: the finished list occupies
+// ent[base .. base + total), ordered by step, whatever the number of windows.
 // ---------------------------------------------------------------------------
-constexpr int kListStepsPerLane = kMaxStepsPerChunk / 64;
+constexpr int kListStepsPerLane = 4;
+constexpr int kListWindow = 64 * kListStepsPerLane;
+
+struct BeamMap {
+    uint32_t lo, hi;   // slots of beams 0..3 and 4..7, one byte each
+};
+constexpr uint32_t kIdBytesLo = 0x03020100u;
+constexpr uint32_t kIdBytesHi = 0x07060504u;
+
+// (f o g)[j] = f[g[j]]: the bytes of g select among the eight bytes of f
+__device__ __forceinline__ BeamMap bm_compose(BeamMap f, BeamMap g)
+{
+    return BeamMap{__builtin_amdgcn_perm(f.hi, f.lo, g.lo), __builtin_amdgcn_perm(f.hi, f.lo, g.hi)};
+}
+__device__ __forceinline__ uint32_t bm_get(BeamMap f, int j)
+{
+    return ((j < 4 ? f.lo : f.hi) >> (8 * (j & 3))) & 0xffu;
+}
+__device__ __forceinline__ BeamMap bm_shfl_down(BeamMap f, int off)
+{
+    return BeamMap{(uint32_t)__shfl_down((int)f.lo, off), (uint32_t)__shfl_down((int)f.hi, off)};
+}
+__device__ __forceinline__ BeamMap bm_broadcast(BeamMap f, int src)
+{
+    return BeamMap{(uint32_t)__shfl((int)f.lo, src), (uint32_t)__shfl((int)f.hi, src)};
+}
+// entries are trusted to lie in [0, W); clamping keeps a bad table inside the
+// request's own rows instead of reading past the buffers
+__device__ __forceinline__ BeamMap bm_pack(const ParentRow& r, int W)
+{
+    uint32_t w[2] = {kIdBytesLo, kIdBytesHi};
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+        if (x < W) {
+            const uint32_t v = (uint32_t)min(max(r.v[x], 0), W - 1);
+            w[x >> 2] = (w[x >> 2] & ~(0xffu << (8 * (x & 3)))) | (v << (8 * (x & 3)));
+        }
+    }
+    return BeamMap{w[0], w[1]};
+}
+
+// Inclusive suffix composition over the lanes of a wave: lane i ends up with
+// x_i o x_{i+1} o ... o x_63.
+__device__ __forceinline__ BeamMap wave_suffix_compose(BeamMap x, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const BeamMap o = bm_shfl_down(x, off);
+        const BeamMap c = bm_compose(x, o);
+        if (lane + off < 64) x = c;
+    }
+    return x;
+}
 
 struct ListRows {
     ParentRow r[kListStepsPerLane];
 };
 
-// Requests the parent rows the builder lane needs (step s0+t+1 for its steps
-// t < n-1); other slots are pointed at the last valid row and ignored later, so
-// that no load is conditional.  Requires W > 1 (parent non-null) and T >= 1.
+// Requests the parent rows lane `lane` needs for the window that starts at step
+// `a`: row a+t+1 for its steps t = 4 lane .. 4 lane + 3.  Rows past the table are
+// pointed at the last valid row and ignored later, so that no load is
+// conditional.  Requires W > 1 (parent non-null) and T >= 1.
 __device__ __forceinline__ void load_list_rows(ListRows& rows, const int32_t* parent, int N, int W,
-                                               int T, int b, int s0, int lane)
+                                               int T, int b, int a, int lane)
 {
 #pragma unroll
     for (int k = 0; k < kListStepsPerLane; ++k) {
-        const int s = min(s0 + kListStepsPerLane * lane + k + 1, T - 1);
+        const int s = min(a + kListStepsPerLane * lane + k + 1, T - 1);
         rows.r[k] = load_parent_row(parent, N, W, b, s);
     }
 }
 
-// Inclusive suffix composition over the lanes of a wave: lane i ends up with
-// x_i o x_{i+1} o ... o x_63.
-__device__ __forceinline__ uint32_t wave_suffix_compose(uint32_t x, int lane)
+// First step of the last window of the chunk [s0, s1): the rows a kernel should
+// request early (load_list_rows) and hand to build_response_list_wave.
+__device__ __forceinline__ int list_last_window_start(int s0, int s1)
 {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_down(x, off);
-        if (lane + off < 64) x = map_compose(x, o);
-    }
-    return x;
+    return s0 + ((s1 - s0 - 1) / kListWindow) * kListWindow;
 }
 
-// Called by all 64 lanes of exactly one wave.  `rows` from load_list_rows()
-// (ignored when W == 1).  Ends with a release store to sm.ready.
-__device__ void build_response_list_wave(ResponseListSmem& sm, const int32_t* parent,
+template <int CAP>
+struct WaveListSmem {
+    uint32_t ent[CAP];   // (local step << 16) | (slot << 8) | beam mask
+    int total;
+    int base;            // the list is ent[base .. base + total)
+    int ready;           // set (release) once the three above are final
+};
+
+// Called by all 64 lanes of exactly one wave.  Requires (s1 - s0) * W <= CAP and
+// s1 - s0 < 65536.  `first_rows`: load_list_rows() of the window that starts at
+// list_last_window_start(s0, s1) (ignored when W == 1).
+template <int CAP>
+__device__ void build_response_list_wave(WaveListSmem<CAP>& sm, const int32_t* parent,
                                          int32_t* anc_out, int B, int W, int T, int b, int s0,
-                                         int s1, const ListRows& rows, int lane)
+                                         int s1, const ListRows& first_rows, int lane)
 {
     constexpr int SPL = kListStepsPerLane;
-    const int n = s1 - s0;
+    const int n_all = s1 - s0;
     const int N = B * W;
     if (W == 1) {
-#pragma unroll
-        for (int k = 0; k < SPL; ++k) {
-            const int t = SPL * lane + k;
-            if (t < n) {
-                sm.ent[t] = ((uint32_t)t << 16) | 1u;
-                if (anc_out) anc_out[(size_t)(s0 + t) * N + b] = 0;
-            }
+        for (int t = lane; t < n_all; t += 64) {
+            sm.ent[t] = ((uint32_t)t << 16) | 1u;
+            if (anc_out) anc_out[(size_t)(s0 + t) * N + b] = 0;
         }
-        if (lane == 0) sm.total = n;
+        if (lane == 0) {
+            sm.total = n_all;
+            sm.base = 0;
+        }
         __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         return;
     }
 
-    // (1) carry = A_{s1-1} = P_{s1} o ... o P_{T-1}
-    uint32_t carry = kIdentityMap;
-    const int later = T - s1;
-    if (later > 0) {
+    // slot map of the step that follows the chunk, A_{s1} = P_{s1+1} o ... o P_{T-1}
+    // (only needed when the chunk does not end at T)
+    BeamMap a_next = {kIdBytesLo, kIdBytesHi};
+    if (s1 < T) {
+        const int later = T - 1 - s1;
         const int per = (later + 63) / 64;
-        const int lo = s1 + lane * per;
+        const int lo = s1 + 1 + lane * per;
         const int hi = min(lo + per, T);
-        uint32_t c = kIdentityMap;
-        for (int s = lo; s < hi; ++s) c = map_compose(c, load_parent_map(parent, N, W, b, s));
-        carry = __shfl(wave_suffix_compose(c, lane), 0);
+        BeamMap c = {kIdBytesLo, kIdBytesHi};
+        for (int s = lo; s < hi; ++s) c = bm_compose(c, bm_pack(load_parent_row(parent, N, W, b, s), W));
+        a_next = bm_broadcast(wave_suffix_compose(c, lane), 0);
     }
 
-    // (2) y_t = P_{s0+t+1} (t < n-1), y_{n-1} = carry; A_t = y_t o y_{t+1} o ... o y_{n-1}
-    uint32_t suf[SPL];                                 // suffix inside the lane
-#pragma unroll
-    for (int k = SPL - 1; k >= 0; --k) {
-        const int t = SPL * lane + k;
-        uint32_t y = kIdentityMap;
-        if (t < n - 1) y = pack_parent_row(rows.r[k], W);
-        else if (t == n - 1) y = carry;
-        suf[k] = (k == SPL - 1) ? y : map_compose(y, suf[k + 1]);
-    }
-    const uint32_t incl = wave_suffix_compose(suf[0], lane);
-    uint32_t after = __shfl_down(incl, 1);             // composition of all later lanes
-    if (lane == 63) after = kIdentityMap;
+    int top = CAP;
+    ListRows rows = first_rows;
+    for (int a = list_last_window_start(s0, s1); a >= s0; a -= kListWindow) {
+        const int bnd = min(a + kListWindow, s1);          // window [a, bnd)
+        const int n = bnd - a;
+        ListRows next_rows;
+        if (a > s0) load_list_rows(next_rows, parent, N, W, T, b, a - kListWindow, lane);
 
-    // (3) distinct slots per step, exclusive prefix sum of their counts
-    uint32_t A[SPL], present[SPL];
-    int mine = 0;
+        // y_t = P_{a+t+1} for t < n-1; y_{n-1} = P_bnd o A_bnd (identity when bnd == T);
+        // A_{a+t} = y_t o y_{t+1} o ... o y_{n-1}
+        BeamMap suf[SPL];
 #pragma unroll
-    for (int k = 0; k < SPL; ++k) {
-        A[k] = (k == 0) ? incl : map_compose(suf[k], after);
-        present[k] = 0;
-        if (SPL * lane + k < n) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (j < W) present[k] |= 1u << map_get(A[k], j);
+        for (int k = SPL - 1; k >= 0; --k) {
+            const int t = SPL * lane + k;
+            BeamMap y = {kIdBytesLo, kIdBytesHi};
+            if (t < n && a + t + 1 < T) {
+                y = bm_pack(rows.r[k], W);
+                if (t == n - 1) y = bm_compose(y, a_next);
+            }
+            suf[k] = (k == SPL - 1) ? y : bm_compose(y, suf[k + 1]);
         }
-        mine += __popc(present[k]);
-    }
-    int c = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(c, off);
-        if (lane >= off) c += o;
-    }
-    int pos = c - mine;
-    if (lane == 63) sm.total = c;
+        const BeamMap incl = wave_suffix_compose(suf[0], lane);
+        BeamMap after = bm_shfl_down(incl, 1);             // composition of all later lanes
+        if (lane == 63) after = BeamMap{kIdBytesLo, kIdBytesHi};
+        a_next = bm_broadcast(incl, 0);                    // A_a, for the window below
 
-    // (4) entries, and the resolved table if asked for
+        // per step: byte u of (mlo, mhi) = mask of the beams that sit on slot u
+        BeamMap A[SPL];
+        uint32_t mlo[SPL], mhi[SPL];
+        int mine = 0;
 #pragma unroll
-    for (int k = 0; k < SPL; ++k) {
-        const int t = SPL * lane + k;
-        if (t < n) {
+        for (int k = 0; k < SPL; ++k) {
+            A[k] = (k == 0) ? incl : bm_compose(suf[k], after);
+            mlo[k] = 0;
+            mhi[k] = 0;
+            if (SPL * lane + k < n) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (present[k] & (1u << u)) {
-                    uint32_t mask = 0;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (j < W && map_get(A[k], j) == (uint32_t)u) mask |= 1u << j;
-                    sm.ent[pos++] = ((uint32_t)t << 16) | ((uint32_t)u << 8) | mask;
+                for (int j = 0; j < 8; ++j) {
+                    if (j < W) {
+                        const uint32_t slot = bm_get(A[k], j);
+                        const uint32_t bit = (1u << j) << (8 * (slot & 3));
+                        mlo[k] |= slot < 4 ? bit : 0u;
+                        mhi[k] |= slot < 4 ? 0u : bit;
+                    }
                 }
             }
-            if (anc_out) {
+            // number of non-zero bytes
+            const uint32_t nzl = (mlo[k] | ((mlo[k] & 0x7f7f7f7fu) + 0x7f7f7f7fu)) & 0x80808080u;
+            const uint32_t nzh = (mhi[k] | ((mhi[k] & 0x7f7f7f7fu) + 0x7f7f7f7fu)) & 0x80808080u;
+            mine += __popc(nzl) + __popc(nzh);
+        }
+        int c = mine;
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (j < W)
-                        anc_out[(size_t)(s0 + t) * N + (size_t)b * W + j] = (int32_t)map_get(A[k], j);
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(c, off);
+            if (lane >= off) c += o;
+        }
+        top -= __shfl(c, 63);                              // this window's rows go below the later ones
+        int pos = top + c - mine;
+
+#pragma unroll
+        for (int k = 0; k < SPL; ++k) {
+            const int t = SPL * lane + k;
+            if (t < n) {
+                const uint32_t step = (uint32_t)(a - s0 + t) << 16;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t mask = ((u < 4 ? mlo[k] : mhi[k]) >> (8 * (u & 3))) & 0xffu;
+                    if (mask) sm.ent[pos++] = step | ((uint32_t)u << 8) | mask;
+                }
+                if (anc_out) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (j < W)
+                            anc_out[(size_t)(a + t) * N + (size_t)b * W + j] = (int32_t)bm_get(A[k], j);
+                }
             }
         }
+        rows = next_rows;
+    }
+    if (lane == 0) {
+        sm.total = CAP - top;
+        sm.base = top;
     }
     __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // Any other wave: blocks until the builder wave has published the list (the
-// builder never waits for anything, so this ends), returns the row count.
-__device__ __forceinline__ int wait_response_list(ResponseListSmem& sm)
+// builder never waits for anything, so this ends).
+template <int CAP>
+__device__ __forceinline__ void wait_response_list(WaveListSmem<CAP>& sm)
 {
     while (__hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
         __builtin_amdgcn_s_sleep(2);
-    return sm.total;
 }
 
 }  // namespace segkv

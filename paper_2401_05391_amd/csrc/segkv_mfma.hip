@@ -99,7 +99,9 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 
     __shared__ __align__(16) unsigned char s_region[NW * REGIONB];
     __shared__ __align__(16) unsigned char s_q[QT * ROWB];   // Q^T operand, shared by the waves
-    __shared__ ResponseListSmem s_list;
+    constexpr int LISTCAP = mfma_list_capacity(D, QT);
+    static_assert(NW == kMfmaWaves, "the LDS budget assumes 8 waves");
+    __shared__ WaveListSmem<LISTCAP> s_list;
     __shared__ float s_ml[NW][QT][2];
     __shared__ int s_next_tile;                        // next unclaimed tile of the stream
 
@@ -175,7 +177,8 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     const bool has_resp = s1 > s0;                              // uniform over the work-group
     const bool is_builder = has_resp && wave == NW - 1;         // uniform over the wave
     ListRows lrows;
-    if (is_builder && p.W > 1) load_list_rows(lrows, p.parent, N, p.W, p.T, b, s0, lane);
+    if (is_builder && p.W > 1)
+        load_list_rows(lrows, p.parent, N, p.W, p.T, b, list_last_window_start(s0, s1), lane);
 
     // ---- fused append: the block that owns step T-1 copies the unit's new rows.
     // One (K, V) vector pair per thread; only the loads are issued here, the
@@ -195,6 +198,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
         app_v = load16(p.v_new + src);
     }
 
+    const uint32_t* ent = s_list.ent;                  // start of the response list, once it is known
     SEGKV_PHASE_DECL;
     // ---- running state: reference max and partial sum per lane, O^T accumulators ----
     float m_ref = kEmptyMax;
@@ -282,10 +286,10 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 #pragma unroll
             for (int r = 0; r < NSR; ++r) {
                 const int e = base + key_row(r);
-                const uint32_t ent = s_list.ent[min(e, total - 1)];
-                const int kpos = p.Lp + s0 + (int)(ent >> 16);
+                const uint32_t en = ent[min(e, total - 1)];
+                const int kpos = p.Lp + s0 + (int)(en >> 16);
                 const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
-                const bool vis = (e < total) && ((ent >> qbeam) & 1u);
+                const bool vis = (e < total) && ((en >> qbeam) & 1u);
                 s[r] = vis ? z : -INFINITY;
                 m_tile = fmaxf(m_tile, s[r]);
             }
@@ -406,7 +410,9 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
     bool list_known = !has_resp;
     auto need_list = [&]() {
         if (!list_known) {
-            total = wait_response_list(s_list);
+            wait_response_list(s_list);
+            total = s_list.total;
+            ent = s_list.ent + s_list.base;
             n_tiles = n_ptiles + (total + KT - 1) / KT;
             list_known = true;
         }
@@ -422,9 +428,9 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int e = min(base + RPI * i + srow, total - 1);
-            const uint32_t ent = s_list.ent[e];
-            const int s = s0 + (int)(ent >> 16);
-            const int slot = (int)((ent >> 8) & 0xffu);
+            const uint32_t en = ent[e];
+            const int s = s0 + (int)(en >> 16);
+            const int slot = (int)((en >> 8) & 0xffu);
             // one load per operand through a selected pointer (two loads under
             // divergent branches would have to wait for each other)
             const bool is_new = have_new && s == p.T - 1;

@@ -138,6 +138,33 @@ def test_response_longer_than_one_chunk(T, W, path, planner_env):
     _check(wl, x, res, *ref, what=wl.name)
 
 
+LONG_SINGLE_LAUNCH = [
+    # T, W, Hq, Hkv, D, parents: the response list of one work-group spans several
+    # 256-step windows; "identity" keeps every beam on its own lineage, the worst
+    # case for the list (W distinct rows per step)
+    (300, 4, 2, 2, 64, "uniform"),
+    (700, 4, 2, 2, 128, "identity"),
+    (1100, 4, 4, 4, 64, "uniform"),
+    (513, 2, 2, 1, 256, "uniform"),
+    (330, 8, 2, 2, 128, "uniform"),
+    (800, 4, 16, 2, 128, "identity"),      # 32 queries per KV head: the 32-slot shape, list nearly full
+    (256, 4, 2, 2, 128, "zeros"),
+]
+
+
+@pytest.mark.parametrize("T,W,Hq,Hkv,D,parents", LONG_SINGLE_LAUNCH)
+def test_long_response_in_one_work_group(T, W, Hq, Hkv, D, parents, planner_env):
+    # force the single-launch plan (one work-group walks prompt and response)
+    planner_env(SEGKV_PATH="mfma", SEGKV_TARGET_GROUPS=1)
+    wl = Workload(f"long{T}w{W}d{D}", B=2, W=W, Hq=Hq, Hkv=Hkv, D=D, Lp=70, T=T, parents=parents,
+                  seed=300 + T + W)
+    x = make_inputs(wl)
+    ref = oracle_reference(wl, x)
+    res = run_gpu(wl, x, fused=True)
+    assert res["workspace_bytes"] == 0, "expected the single-launch plan"
+    _check(wl, x, res, *ref, what=wl.name)
+
+
 @pytest.mark.parametrize("path", ["alu", "mfma"])
 def test_run_twice_is_bit_identical(path, planner_env):
     planner_env(SEGKV_PATH=path)
