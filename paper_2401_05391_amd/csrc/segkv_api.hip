@@ -15,6 +15,7 @@ struct Plan {
     int G, nq, QB, n_qblocks;
     int HP;   // adjacent KV heads handled by one wave-wide load (ALU path)
     int mfma; // 1: matrix-core kernel, 0: vector-ALU kernel
+    int NW;   // waves per work-group of the matrix-core kernel
     int merged, n_chunks, pchunk, rchunk, n_rchunks, n_pchunks;
     size_t ws_ml_bytes, ws_acc_bytes;
     unsigned grid;
@@ -100,7 +101,16 @@ Plan make_plan(const segkv_dims* d)
     // per step, at most kMaxListEntries (step, slot) rows.
     int max_steps, max_steps_merged;
     if (pl.mfma) {
-        max_steps_merged = segkv::mfma_list_capacity(d->D, pl.QB) / d->beam;
+        // Four-wave work-groups, two per CU, when there are at least two rounds of
+        // units: one group's start-up and merge then overlap the other's streaming.
+        pl.NW = 8;
+        const long kv_units = (long)d->B * d->Hkv * ceil_div(pl.nq, pl.QB);
+        const int nw_env = env_int("SEGKV_MFMA_WAVES", 0);
+        if (pl.QB == 16 && d->D <= 128 &&
+            (nw_env == 4 || (nw_env == 0 && kv_units >= 512 &&
+                             d->T * d->beam <= segkv::mfma_list_capacity(d->D, pl.QB, 4))))
+            pl.NW = 4;
+        max_steps_merged = segkv::mfma_list_capacity(d->D, pl.QB, pl.NW) / d->beam;
         if (max_steps_merged > 65535) max_steps_merged = 65535;
         max_steps = max_steps_merged < segkv::kMaxStepsPerChunk ? max_steps_merged
                                                                 : segkv::kMaxStepsPerChunk;
@@ -243,7 +253,7 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
 #endif
 
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, d->D, pl.QB, pl.grid, st)
+    hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, d->D, pl.QB, pl.NW, pl.grid, st)
                            : segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.HP, pl.grid, st);
     if (e != hipSuccess) return SEGKV_HIP_ERROR;
     if (pl.n_chunks > 1) {

@@ -61,10 +61,10 @@ struct RopeParams {
 
 constexpr int kMaxStepsPerChunk = 256;   // response steps one work-group can resolve
 constexpr int kMaxListEntries = 1024;    // (step, slot) rows of one chunk: steps * beam <= this
-// LDS budget of the matrix-core decode kernel (8 waves; 160 KB per work-group):
-// whatever the tiles, the Q tile and the merge statistics leave is the response
-// list, whose capacity bounds the response steps one work-group can walk.
-constexpr int kMfmaWaves = 8;
+// LDS budget of the matrix-core decode kernel: 8 waves with the whole 160 KB of a
+// CU, or 4 waves with half of it so that two work-groups share a CU.  Whatever
+// the tiles, the Q tile and the merge statistics leave is the response list,
+// whose capacity bounds the response steps one work-group can walk.
 constexpr int mfma_key_tile(int D) { return D == 256 ? 16 : 32; }
 constexpr int mfma_region_bytes(int D, int QT)
 {
@@ -72,17 +72,18 @@ constexpr int mfma_region_bytes(int D, int QT)
     const int merge = QT * (D + 4) * 4;
     return tiles > merge ? tiles : merge;
 }
-constexpr int mfma_list_capacity(int D, int QT)
+constexpr int mfma_list_capacity(int D, int QT, int NW)
 {
-    const int fixed = kMfmaWaves * mfma_region_bytes(D, QT) + QT * (2 * D + 16) + kMfmaWaves * QT * 8 + 64;
-    const int cap = (160 * 1024 - 256 - fixed) / 4;
-    return (cap > 16384 ? 16384 : cap) & ~63;
+    const int fixed = NW * mfma_region_bytes(D, QT) + QT * (2 * D + 16) + NW * QT * 8 + 64;
+    const int budget = (NW == 8 ? 160 : 80) * 1024 - 256;
+    const int cap = (budget - fixed) / 4;
+    return cap < 64 ? 0 : ((cap > 16384 ? 16384 : cap) & ~63);
 }
 constexpr int kProbeGroups = 4096;       // work-groups (and sink words) of the read probe
 
 hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, int HP, unsigned grid,
                               hipStream_t st);
-hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, unsigned grid,
+hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, int NW, unsigned grid,
                                    hipStream_t st);
 hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st);
 hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_acc, int NQ, int D,

@@ -84,7 +84,8 @@ struct DecodeGeometry {
 };
 
 template <int D, int NW, int DEPTH, int QT>
-__global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void sdpa_decode_mfma_kernel(SdpaParams p)
 {
     using Geo = DecodeGeometry<D, QT>;
     constexpr int KT = Geo::KT, CPR = Geo::CPR, RPI = Geo::RPI, NLD = Geo::NLD;
@@ -99,8 +100,8 @@ __global__ __launch_bounds__(NW * 64) void sdpa_decode_mfma_kernel(SdpaParams p)
 
     __shared__ __align__(16) unsigned char s_region[NW * REGIONB];
     __shared__ __align__(16) unsigned char s_q[QT * ROWB];   // Q^T operand, shared by the waves
-    constexpr int LISTCAP = mfma_list_capacity(D, QT);
-    static_assert(NW == kMfmaWaves, "the LDS budget assumes 8 waves");
+    constexpr int LISTCAP = mfma_list_capacity(D, QT, NW);
+    static_assert(LISTCAP >= 64, "no room for a response list");
     __shared__ WaveListSmem<LISTCAP> s_list;
     __shared__ float s_ml[NW][QT][2];
     __shared__ int s_next_tile;                        // next unclaimed tile of the stream
@@ -600,17 +601,21 @@ static void launch_variant(const SdpaParams& p, unsigned grid, hipStream_t st)
                        p);
 }
 
-hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, unsigned grid, hipStream_t st)
+hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, int NW, unsigned grid,
+                                   hipStream_t st)
 {
-    if (QT != 16 && QT != 32) return hipErrorInvalidValue;
+    if ((QT != 16 && QT != 32) || (NW != 8 && NW != 4)) return hipErrorInvalidValue;
+    if (NW == 4 && (QT != 16 || D > 128)) return hipErrorInvalidValue;
     switch (D) {
         case 64:
-            if (QT == 32) launch_variant<64, 8, 1, 32>(p, grid, st);
-            else          launch_variant<64, 8, 1, 16>(p, grid, st);
+            if (QT == 32)     launch_variant<64, 8, 1, 32>(p, grid, st);
+            else if (NW == 8) launch_variant<64, 8, 1, 16>(p, grid, st);
+            else              launch_variant<64, 4, 1, 16>(p, grid, st);
             break;
         case 128:
-            if (QT == 32) launch_variant<128, 8, 1, 32>(p, grid, st);
-            else          launch_variant<128, 8, 1, 16>(p, grid, st);
+            if (QT == 32)     launch_variant<128, 8, 1, 32>(p, grid, st);
+            else if (NW == 8) launch_variant<128, 8, 1, 16>(p, grid, st);
+            else              launch_variant<128, 4, 1, 16>(p, grid, st);
             break;
         case 256:
             if (QT == 32) return hipErrorInvalidValue;   // accumulators would not fit: planner uses 16

@@ -25,6 +25,7 @@ def _announce(request):
 def planner_env():
     """Temporarily force the launch planner (chunking) through its documented knobs."""
     saved = {k: os.environ.get(k) for k in ("SEGKV_TARGET_GROUPS", "SEGKV_MIN_PCHUNK", "SEGKV_PATH",
+                                             "SEGKV_MFMA_WAVES",
                                             "SEGKV_HEADS_PER_WAVE")}
 
     def set_env(**kw):
@@ -163,6 +164,22 @@ def test_long_response_in_one_work_group(T, W, Hq, Hkv, D, parents, planner_env)
     res = run_gpu(wl, x, fused=True)
     assert res["workspace_bytes"] == 0, "expected the single-launch plan"
     _check(wl, x, res, *ref, what=wl.name)
+
+
+@pytest.mark.parametrize("wl", [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[7], SMALL[8], SMALL[10],
+                                SMALL[11], SMALL[14]], ids=lambda w: w.name)
+@pytest.mark.parametrize("merged", [False, True])
+def test_four_wave_work_groups(wl, merged, planner_env):
+    # the two-groups-per-CU variant of the 16-slot shape, which the planner only
+    # picks for large batches: forced here on small cases, chunked and single-launch
+    if merged:
+        planner_env(SEGKV_PATH="mfma", SEGKV_MFMA_WAVES=4, SEGKV_TARGET_GROUPS=1)
+    else:
+        planner_env(SEGKV_PATH="mfma", SEGKV_MFMA_WAVES=4, SEGKV_TARGET_GROUPS=64, SEGKV_MIN_PCHUNK=32)
+    x = make_inputs(wl)
+    ref = oracle_reference(wl, x)
+    res = run_gpu(wl, x, fused=True)
+    _check(wl, x, res, *ref, what=f"{wl.name}/4 waves")
 
 
 @pytest.mark.parametrize("path", ["alu", "mfma"])
