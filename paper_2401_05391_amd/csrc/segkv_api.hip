@@ -101,13 +101,13 @@ Plan make_plan(const segkv_dims* d)
     // per step, at most kMaxListEntries (step, slot) rows.
     int max_steps, max_steps_merged;
     if (pl.mfma) {
-        // Four-wave work-groups, two per CU, when there are at least two rounds of
-        // units: one group's start-up and merge then overlap the other's streaming.
+        // Four-wave work-groups, two per CU, when there are more units than CUs: one
+        // group's start-up and merge then overlap the other's streaming.
         pl.NW = 8;
         const long kv_units = (long)d->B * d->Hkv * ceil_div(pl.nq, pl.QB);
         const int nw_env = env_int("SEGKV_MFMA_WAVES", 0);
         if (pl.QB == 16 && d->D <= 128 &&
-            (nw_env == 4 || (nw_env == 0 && kv_units >= 512 &&
+            (nw_env == 4 || (nw_env == 0 && kv_units > 256 &&
                              d->T * d->beam <= segkv::mfma_list_capacity(d->D, pl.QB, 4))))
             pl.NW = 4;
         max_steps_merged = segkv::mfma_list_capacity(d->D, pl.QB, pl.NW) / d->beam;
