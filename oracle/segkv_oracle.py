@@ -125,6 +125,35 @@ def sdpa_decode(q: np.ndarray, prompt_k: np.ndarray, prompt_v: np.ndarray,
     return out, anc, probs
 
 
+def sdpa_decode_ragged(q: np.ndarray, prompt_k: np.ndarray, prompt_v: np.ndarray,
+                       resp_k: np.ndarray, resp_v: np.ndarray, parent: np.ndarray,
+                       W: int, T: int, scale: float, prompt_lens: np.ndarray,
+                       slopes: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-request prompt lengths (a padded static batch): request b owns prompt rows
+    0..prompt_lens[b]-1 of prompt_k[b] / prompt_v[b]; the rows behind them are padding
+    and take no part.  By definition this is the attention of each request taken on
+    its own with Lp = prompt_lens[b] -- which is how it is computed here: one call
+    of sdpa_decode per request on the sliced tensors (positions then follow from the
+    request's own length: response step s sits at prompt_lens[b] + s).
+    Returns (out [B*W, Hq, D] float64, anc [T, B*W] int32)."""
+    N, Hq, D = q.shape
+    B = N // W
+    out = np.empty((N, Hq, D), dtype=np.float64)
+    anc = np.empty((T, N), dtype=np.int32)
+    for b in range(B):
+        rows = slice(b * W, (b + 1) * W)
+        lb = int(prompt_lens[b])
+        o, a, _ = sdpa_decode(np.ascontiguousarray(q[rows]),
+                              np.ascontiguousarray(prompt_k[b:b + 1, :lb]),
+                              np.ascontiguousarray(prompt_v[b:b + 1, :lb]),
+                              np.ascontiguousarray(resp_k[:, rows]),
+                              np.ascontiguousarray(resp_v[:, rows]),
+                              np.ascontiguousarray(parent[:T, rows]), W, T, scale, slopes=slopes)
+        out[rows] = o
+        anc[:, rows] = a
+    return out, anc
+
+
 def sdpa_prefill(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
                  slopes: Optional[np.ndarray] = None, rows: Optional[np.ndarray] = None) -> np.ndarray:
     """fp64 causal prefill attention.  q [B,N0,Hq,D], k/v [B,N0,Hkv,D] fp16.

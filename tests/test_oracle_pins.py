@@ -392,3 +392,30 @@ def test_half_decoding_is_exact_for_every_bit_pattern():
                                        1, 1, 1.0, want_probs=True)
     assert np.array_equal(probs, np.ones((n, 1)))
     assert np.array_equal(out[:, 0], rv[0, :, 0].astype(np.float64))
+
+
+def test_ragged_prompt_lengths_reduce_to_the_batch_call():
+    # per-request lengths: equal lengths reproduce the batch call exactly; shorter ones ignore
+    # whatever sits in the padding rows
+    wl = Workload("ragged", B=3, W=2, Hq=4, Hkv=2, D=8, Lp=9, T=4, alibi=True, seed=77)
+    x = make_inputs(wl)
+    rk, rv = x["resp_k"].copy(), x["resp_v"].copy()
+    oracle.append_kv(rk, rv, x["k_new"], x["v_new"], wl.T - 1)
+    full, anc, _ = oracle.sdpa_decode(x["q"], x["prompt_k"], x["prompt_v"], rk, rv, x["parent"], wl.W,
+                                      wl.T, wl.scale, slopes=x["slopes"])
+    same, anc2 = oracle.sdpa_decode_ragged(x["q"], x["prompt_k"], x["prompt_v"], rk, rv, x["parent"],
+                                           wl.W, wl.T, wl.scale, np.full(wl.B, wl.Lp), slopes=x["slopes"])
+    assert np.array_equal(anc, anc2)
+    np.testing.assert_allclose(same, full, rtol=0, atol=1e-13)
+    lens = np.array([9, 0, 5])
+    a, _ = oracle.sdpa_decode_ragged(x["q"], x["prompt_k"], x["prompt_v"], rk, rv, x["parent"], wl.W,
+                                     wl.T, wl.scale, lens, slopes=x["slopes"])
+    pk2, pv2 = x["prompt_k"].copy(), x["prompt_v"].copy()
+    for b, lb in enumerate(lens):
+        pk2[b, lb:] = np.float16(np.nan)
+        pv2[b, lb:] = np.float16(np.nan)
+    b_, _ = oracle.sdpa_decode_ragged(x["q"], pk2, pv2, rk, rv, x["parent"], wl.W, wl.T, wl.scale, lens,
+                                      slopes=x["slopes"])
+    assert np.array_equal(a, b_) and np.isfinite(a).all()
+    np.testing.assert_allclose(a[0:2], full[0:2], rtol=0, atol=1e-13)       # request 0 is at full length
+    assert np.abs(a[2:] - full[2:]).max() > 1e-3                            # the others are not
