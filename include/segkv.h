@@ -136,6 +136,28 @@ int segkv_sdpa_decode(void* out, const void* q,
                       void* workspace, size_t workspace_bytes,
                       float scale, const segkv_dims* d, void* stream);
 
+/*
+ * The same step for a padded static batch whose requests have prompts of
+ * different lengths (Section 2.2: requests of a batch are padded to one
+ * length).  prompt_lens: NULL (identical to segkv_sdpa_decode), or [B] int32 on
+ * the device: request b owns rows 0 .. prompt_lens[b]-1 of prompt_k[b] /
+ * prompt_v[b] (0 <= prompt_lens[b] <= Lp; values outside are clamped); the
+ * padding rows behind them are never read.  Positions follow the request's own
+ * length: its response step s sits at prompt_lens[b] + s, its query at
+ * prompt_lens[b] + T - 1.  Everything else as in segkv_sdpa_decode; the
+ * workspace size is the same.
+ */
+int segkv_sdpa_decode_ragged(void* out, const void* q,
+                             const void* prompt_k, const void* prompt_v,
+                             void* resp_k, void* resp_v,
+                             const int32_t* parent,
+                             const void* k_new, const void* v_new,
+                             const float* alibi_slopes,
+                             const int32_t* prompt_lens,
+                             int32_t* anc_out,
+                             void* workspace, size_t workspace_bytes,
+                             float scale, const segkv_dims* d, void* stream);
+
 /* Bytes of device scratch segkv_sdpa_decode needs for these dimensions (the
  * split-KV partial results of Section 3.3's accumulate step).  0 on invalid
  * dimensions. */

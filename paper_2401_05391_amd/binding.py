@@ -25,7 +25,7 @@ EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_status_string", "segkv_stream_read_probe", "segkv_cache_token_bytes",
            "segkv_cache_standard_bytes", "segkv_cache_segment_bytes", "segkv_response_capacity",
            "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
-           "segkv_rope_append")
+           "segkv_rope_append", "segkv_sdpa_decode_ragged")
 
 
 class SegkvDims(ctypes.Structure):
@@ -60,6 +60,9 @@ def load_library():
     lib.segkv_sdpa_decode.restype = ctypes.c_int
     lib.segkv_sdpa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                                       ctypes.c_float, dp, vp]
+    lib.segkv_sdpa_decode_ragged.restype = ctypes.c_int
+    lib.segkv_sdpa_decode_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
+                                             ctypes.c_float, dp, vp]
     lib.segkv_workspace_bytes.restype = sz
     lib.segkv_workspace_bytes.argtypes = [dp]
     lib.segkv_value_stagger_bytes.restype = sz
@@ -146,6 +149,19 @@ def sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvD
         raise SegkvError(rc, "segkv_sdpa_decode")
 
 
+def sdpa_decode_ragged(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, prompt_lens,
+                       dims: SegkvDims, scale: float, k_new=None, v_new=None, alibi_slopes=None,
+                       anc_out=None, workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load_library().segkv_sdpa_decode_ragged(
+        _ptr(out), _ptr(q), _ptr(prompt_k), _ptr(prompt_v), _ptr(resp_k), _ptr(resp_v),
+        _ptr(parent), _ptr(k_new), _ptr(v_new), _ptr(alibi_slopes), _ptr(prompt_lens),
+        _ptr(anc_out), _ptr(workspace), ws_bytes, float(scale), ctypes.byref(dims),
+        _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_sdpa_decode_ragged")
+
+
 def prepare_sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvDims,
                         scale: float, k_new=None, v_new=None, alibi_slopes=None, anc_out=None,
                         workspace=None, stream=None):
@@ -197,7 +213,7 @@ def grow_response(new_k, new_v, old_k, old_v, dims: SegkvDims, stream=None) -> N
                                             _stream_handle(stream))
     if rc != SEGKV_OK:
         raise SegkvError(rc, "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
-           "segkv_rope_append")
+           "segkv_rope_append", "segkv_sdpa_decode_ragged")
 
 
 def stream_read_probe(src, sink, stream=None) -> None:

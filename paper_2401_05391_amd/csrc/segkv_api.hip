@@ -208,6 +208,17 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
                       void* workspace, size_t workspace_bytes, float scale, const segkv_dims* d,
                       void* stream)
 {
+    return segkv_sdpa_decode_ragged(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new, v_new,
+                                    alibi_slopes, nullptr, anc_out, workspace, workspace_bytes, scale,
+                                    d, stream);
+}
+
+int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, const void* prompt_v,
+                             void* resp_k, void* resp_v, const int32_t* parent, const void* k_new,
+                             const void* v_new, const float* alibi_slopes,
+                             const int32_t* prompt_lens, int32_t* anc_out, void* workspace,
+                             size_t workspace_bytes, float scale, const segkv_dims* d, void* stream)
+{
     if (!dims_ok(d)) return SEGKV_INVALID_ARG;
     if (!out || !q || !resp_k || !resp_v) return SEGKV_INVALID_ARG;
     if (d->Lp > 0 && (!prompt_k || !prompt_v)) return SEGKV_INVALID_ARG;
@@ -218,7 +229,8 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
     if (misaligned(out) || misaligned(q) || misaligned(resp_k) || misaligned(resp_v) ||
         (d->Lp > 0 && (misaligned(prompt_k) || misaligned(prompt_v))) ||
         (k_new && (misaligned(k_new) || misaligned(v_new))) || misaligned(workspace) ||
-        ((uintptr_t)parent & 3u) || ((uintptr_t)alibi_slopes & 3u) || ((uintptr_t)anc_out & 3u))
+        ((uintptr_t)parent & 3u) || ((uintptr_t)alibi_slopes & 3u) || ((uintptr_t)anc_out & 3u) ||
+        ((uintptr_t)prompt_lens & 3u))
         return SEGKV_MISALIGNED;
 
     const Plan pl = make_plan(d);
@@ -236,6 +248,7 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
     p.k_new = (const _Float16*)k_new;
     p.v_new = (const _Float16*)v_new;
     p.slopes = alibi_slopes;
+    p.prompt_lens = prompt_lens;
     p.anc_out = anc_out;
     p.ws_ml = need ? (float*)workspace : nullptr;
     p.ws_acc = need ? (float*)((char*)workspace + pl.ws_ml_bytes) : nullptr;

@@ -118,16 +118,18 @@ void sdpa_decode_alu_kernel(SdpaParams p)
 
     // merged: one work-group walks the whole prompt and the whole response;
     // otherwise a chunk is a slice of response steps or of prompt positions.
+    // valid prompt rows of this request (a padded batch passes per-request lengths)
+    const int Lp = p.prompt_lens ? min(max(p.prompt_lens[b], 0), p.Lp) : p.Lp;
     int k0 = 0, k1 = 0, s0 = 0, s1 = 0;
     if (p.merged) {
-        k1 = p.Lp;
+        k1 = Lp;
         s1 = p.T;
     } else if (chunk < p.n_rchunks) {
         s0 = chunk * p.rchunk;
         s1 = min(s0 + p.rchunk, p.T);
     } else {
-        k0 = (chunk - p.n_rchunks) * p.pchunk;
-        k1 = min(k0 + p.pchunk, p.Lp);
+        k0 = min((chunk - p.n_rchunks) * p.pchunk, Lp);
+        k1 = min(k0 + p.pchunk, Lp);
     }
     const bool direct_out = (p.n_chunks == 1);
 
@@ -153,7 +155,7 @@ void sdpa_decode_alu_kernel(SdpaParams p)
             qv[qi][v * 4 + 3] = as_half2(w.w);
         }
     }
-    const int qpos = p.Lp + p.T - 1;
+    const int qpos = Lp + p.T - 1;
 
     // ---- fused append: the block that owns step T-1 copies its heads' new rows ----
     const bool have_new = (p.k_new != nullptr);
@@ -298,7 +300,7 @@ void sdpa_decode_alu_kernel(SdpaParams p)
                     t.k[u][v] = load16_stream(kp + v * (LPR * 8));
                     t.v[u][v] = load16_stream(vp + v * (LPR * 8));
                 }
-                t.meta[u] = ((uint32_t)(p.Lp + s) << 8) | (ok ? (ent & 0xffu) : 0u);
+                t.meta[u] = ((uint32_t)(Lp + s) << 8) | (ok ? (ent & 0xffu) : 0u);
             }
         };
         stream_tiles_impl<Tile>(fetch, consume, wave, n_tiles);

@@ -18,6 +18,7 @@ struct SdpaParams {
     const _Float16* k_new;
     const _Float16* v_new;
     const float* slopes;
+    const int32_t* prompt_lens;   // [B] valid prompt rows per request, or null (all Lp)
     int32_t* anc_out;
     float* ws_ml;    // [n_chunks][NQ][2]
     float* ws_acc;   // [n_chunks][NQ][D]

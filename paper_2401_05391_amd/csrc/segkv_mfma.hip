@@ -83,7 +83,7 @@ struct DecodeGeometry {
     static_assert(QT == 16 || KT == 32, "the 32-slot shape multiplies 32-key tiles");
 };
 
-template <int D, int NW, int DEPTH, int QT>
+template <int D, int NW, int QT>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void sdpa_decode_mfma_kernel(SdpaParams p)
 {
@@ -129,16 +129,18 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     const int b = id / p.n_chunks;
     const int N = p.B * p.W;
 
+    // valid prompt rows of this request (a padded batch passes per-request lengths)
+    const int Lp = p.prompt_lens ? min(max(p.prompt_lens[b], 0), p.Lp) : p.Lp;
     int k0 = 0, k1 = 0, s0 = 0, s1 = 0;
     if (p.merged) {
-        k1 = p.Lp;
+        k1 = Lp;
         s1 = p.T;
     } else if (chunk < p.n_rchunks) {
         s0 = chunk * p.rchunk;
         s1 = min(s0 + p.rchunk, p.T);
     } else {
-        k0 = (chunk - p.n_rchunks) * p.pchunk;
-        k1 = min(k0 + p.pchunk, p.Lp);
+        k0 = min((chunk - p.n_rchunks) * p.pchunk, Lp);
+        k1 = min(k0 + p.pchunk, Lp);
     }
     const bool direct_out = (p.n_chunks == 1);
 
@@ -154,7 +156,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     const int qbeam = lqc / p.G;
     const int hq = g * p.G + (lqc % p.G);
     const float slope2 = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
-    const int qpos = p.Lp + p.T - 1;
+    const int qpos = Lp + p.T - 1;
     // Requests that later steps depend on go out first, in this order: the Q
     // chunks this thread stages, its row of the parent table, then (below) the
     // wave's first key tile.  They are consumed in the same order, so each wait
@@ -288,7 +290,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             for (int r = 0; r < NSR; ++r) {
                 const int e = base + key_row(r);
                 const uint32_t en = ent[min(e, total - 1)];
-                const int kpos = p.Lp + s0 + (int)(en >> 16);
+                const int kpos = Lp + s0 + (int)(en >> 16);
                 const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
                 const bool vis = (e < total) && ((en >> qbeam) & 1u);
                 s[r] = vis ? z : -INFINITY;
@@ -458,22 +460,18 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         }
     };
 
-    // DEPTH tiles are in flight per wave, each in its own named register set.
-    Staged st_a, st_b;
-    const int n_static = has_resp ? NW - 1 : NW;       // waves with static first tiles
-    int ta = wave;                                     // static first tiles (not for the builder)
-    int tb = wave + n_static;
+    Staged st;
+    const int n_static = has_resp ? NW - 1 : NW;       // waves with a static first tile
+    int ti = wave;                                     // static first tile (not for the builder)
     if (tid == 0) {
-        s_next_tile = DEPTH * n_static;
+        s_next_tile = n_static;
         s_list.ready = 0;
     }
-    // the first tiles need nothing but addresses when they are prompt tiles
-    const bool early_a = !is_builder && ta < n_ptiles;
-    const bool early_b = DEPTH > 1 && !is_builder && tb < n_ptiles;
-    if (early_a) fetch_prompt(st_a, ta);
-    if (early_b) fetch_prompt(st_b, tb);
-    // Q tile to LDS: requested before the tiles above, so waiting for it leaves
-    // them in flight
+    // the first tile needs nothing but addresses when it is a prompt tile
+    const bool early = !is_builder && ti < n_ptiles;
+    if (early) fetch_prompt(st, ti);
+    // Q tile to LDS: requested before the tile above, so waiting for it leaves
+    // the tile in flight
 #pragma unroll
     for (int c = 0; c < QCH; ++c) {
         const int i = tid + c * NT;
@@ -491,21 +489,17 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
                                  p.W, p.T, b, s0, s1, lrows, lane);
         need_list();
         SEGKV_STAMP(2);
-        ta = claim_tile();
-        if (DEPTH > 1) tb = claim_tile();
+        ti = claim_tile();
     }
-    if (!early_a) {
-        if (ta >= n_ptiles) need_list();
-        fetch(st_a, ta);
-    }
-    if (DEPTH > 1 && !early_b) {
-        if (tb >= n_ptiles) need_list();
-        fetch(st_b, tb);
+    if (!early) {
+        if (ti >= n_ptiles) need_list();
+        fetch(st, ti);
     }
     SEGKV_PHASE_BEGIN;
-    // One turn: the set's tile has landed -> LDS, the set is refilled with the
-    // next claimed tile, the tile in LDS is multiplied.
-    auto turn = [&](Staged& st, int& ti) __attribute__((always_inline)) {
+    // One turn: the tile has landed -> LDS, the registers are refilled with the
+    // next claimed tile, the tile in LDS is multiplied.  (Two tiles in flight per
+    // wave measured slower: the CU's outstanding-load limit, not the wave's, binds.)
+    while (ti < n_tiles) {
         stage_to_lds(st);
         SEGKV_STAMP_FIRST(3);
         const int nxt = claim_tile();
@@ -514,17 +508,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         SEGKV_PHASE(0);
         process(ti);
         ti = nxt;
-    };
-    // claims only grow, so the first set that runs dry ends the stream
-    if (DEPTH == 1) {
-        while (ta < n_tiles) turn(st_a, ta);
-    } else {
-        while (true) {
-            if (ta >= n_tiles) break;
-            turn(st_a, ta);
-            if (tb >= n_tiles) break;
-            turn(st_b, tb);
-        }
     }
     SEGKV_PHASE_DUMP;
 
@@ -594,10 +577,10 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
 // ---------------------------------------------------------------------------
 // Host-side launcher
 // ---------------------------------------------------------------------------
-template <int D, int NW, int DEPTH, int QT>
+template <int D, int NW, int QT>
 static void launch_variant(const SdpaParams& p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, DEPTH, QT>), dim3(grid), dim3(NW * 64), 0, st,
+    hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT>), dim3(grid), dim3(NW * 64), 0, st,
                        p);
 }
 
@@ -608,18 +591,18 @@ hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, int NW, u
     if (NW == 4 && (QT != 16 || D > 128)) return hipErrorInvalidValue;
     switch (D) {
         case 64:
-            if (QT == 32)     launch_variant<64, 8, 1, 32>(p, grid, st);
-            else if (NW == 8) launch_variant<64, 8, 1, 16>(p, grid, st);
-            else              launch_variant<64, 4, 1, 16>(p, grid, st);
+            if (QT == 32)     launch_variant<64, 8, 32>(p, grid, st);
+            else if (NW == 8) launch_variant<64, 8, 16>(p, grid, st);
+            else              launch_variant<64, 4, 16>(p, grid, st);
             break;
         case 128:
-            if (QT == 32)     launch_variant<128, 8, 1, 32>(p, grid, st);
-            else if (NW == 8) launch_variant<128, 8, 1, 16>(p, grid, st);
-            else              launch_variant<128, 4, 1, 16>(p, grid, st);
+            if (QT == 32)     launch_variant<128, 8, 32>(p, grid, st);
+            else if (NW == 8) launch_variant<128, 8, 16>(p, grid, st);
+            else              launch_variant<128, 4, 16>(p, grid, st);
             break;
         case 256:
             if (QT == 32) return hipErrorInvalidValue;   // accumulators would not fit: planner uses 16
-            launch_variant<256, 8, 1, 16>(p, grid, st);
+            launch_variant<256, 8, 16>(p, grid, st);
             break;
         default: return hipErrorInvalidValue;
     }

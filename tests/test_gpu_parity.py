@@ -278,3 +278,49 @@ def test_fig6_llama2_13b_shape(bs):
     res = run_gpu(wl, x, fused=True)
     ref_out, ref_anc, ref_rk, ref_rv = oracle_reference(wl, x)
     _check(wl, x, res, ref_out, ref_anc, ref_rk, ref_rv, wl.name)
+
+
+RAGGED = [
+    # workload, per-request prompt lengths (0 = a request without prompt), path, planner knobs
+    (Workload("rag_mfma16", B=4, W=4, Hq=4, Hkv=4, D=128, Lp=200, T=21, seed=401), [200, 0, 37, 129], "mfma", {}),
+    (Workload("rag_mfma32_alibi", B=3, W=4, Hq=16, Hkv=2, D=128, Lp=150, T=30, alibi=True, seed=402), [1, 150, 64], "mfma", {}),
+    (Workload("rag_d256", B=3, W=2, Hq=2, Hkv=2, D=256, Lp=90, T=9, seed=403), [33, 90, 16], "mfma", {}),
+    (Workload("rag_single_launch", B=3, W=4, Hq=4, Hkv=4, D=64, Lp=120, T=40, alibi=True, seed=404), [120, 5, 77], "mfma",
+     dict(SEGKV_TARGET_GROUPS=1)),
+    (Workload("rag_alu", B=4, W=1, Hq=8, Hkv=8, D=128, Lp=300, T=12, parents="identity", alibi=True, seed=405),
+     [300, 0, 31, 257], "alu", {}),
+    (Workload("rag_alu_w4", B=2, W=4, Hq=4, Hkv=4, D=64, Lp=100, T=20, seed=406), [64, 99], "alu", {}),
+]
+
+
+@pytest.mark.parametrize("wl,lens,path,knobs", RAGGED, ids=[c[0].name for c in RAGGED])
+def test_per_request_prompt_lengths(wl, lens, path, knobs, planner_env):
+    import torch
+    import paper_2401_05391_amd as segkv
+    from oracle import segkv_oracle as oracle
+    planner_env(SEGKV_PATH=path, **knobs)
+    x = make_inputs(wl)
+    lens = np.asarray(lens, dtype=np.int32)
+    # padding rows are NaN: they must never be read
+    for b, lb in enumerate(lens):
+        x["prompt_k"][b, lb:] = np.float16(np.nan)
+        x["prompt_v"][b, lb:] = np.float16(np.nan)
+    dev = torch.device("cuda:0")
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    rk, rv = up(x["resp_k"]), up(x["resp_v"])
+    dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+    nbytes = segkv.workspace_bytes(dims)
+    ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=dev) if nbytes else None
+    out = torch.full((wl.N, wl.Hq, wl.D), float("nan"), dtype=torch.float16, device=dev)
+    anc = torch.full((wl.T, wl.N), -1, dtype=torch.int32, device=dev)
+    segkv.sdpa_decode_ragged(out, up(x["q"]), up(x["prompt_k"]), up(x["prompt_v"]), rk, rv, up(x["parent"]),
+                             up(lens), dims, wl.scale, k_new=up(x["k_new"]), v_new=up(x["v_new"]),
+                             alibi_slopes=up(x["slopes"]), anc_out=anc, workspace=ws)
+    torch.cuda.synchronize()
+    ork, orv = x["resp_k"].copy(), x["resp_v"].copy()
+    oracle.append_kv(ork, orv, x["k_new"], x["v_new"], wl.T - 1)
+    ref, ref_anc = oracle.sdpa_decode_ragged(x["q"], x["prompt_k"], x["prompt_v"], ork, orv, x["parent"],
+                                             wl.W, wl.T, wl.scale, lens, slopes=x["slopes"])
+    assert np.array_equal(anc.cpu().numpy(), ref_anc)
+    assert_parity(out.cpu().numpy(), ref, wl.name)
+    assert same_bits(rk.cpu().numpy(), ork) and same_bits(rv.cpu().numpy(), orv)
