@@ -324,3 +324,44 @@ def test_per_request_prompt_lengths(wl, lens, path, knobs, planner_env):
     assert np.array_equal(anc.cpu().numpy(), ref_anc)
     assert_parity(out.cpu().numpy(), ref, wl.name)
     assert same_bits(rk.cpu().numpy(), ork) and same_bits(rv.cpu().numpy(), orv)
+
+
+def _random_workloads(n, seed):
+    """Seeded draw of small shapes across every dimension the planner looks at."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        D = int(rng.choice([64, 128, 256]))
+        W = int(rng.choice([1, 2, 3, 4, 5, 8]))
+        Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        G = int(rng.choice([1, 1, 2, 4, 8]))
+        B = int(rng.integers(1, 6))
+        Lp = int(rng.choice([0, 1, 31, 32, 33, 100, 257, 600]))
+        T = int(rng.choice([1, 2, 15, 16, 17, 64, 130, 300]))
+        # keep the oracle's work small
+        while B * W * Hkv * G * (Lp + T) * D > 6e7:
+            B = max(1, B - 1)
+            Lp //= 2
+        out.append(Workload(f"rnd{seed}_{i}", B=B, W=W, Hq=Hkv * G, Hkv=Hkv, D=D, Lp=Lp, T=T,
+                            alibi=bool(rng.integers(0, 2)),
+                            parents="identity" if W == 1 else str(rng.choice(["uniform", "uniform", "identity", "zeros"])),
+                            seed=1000 * seed + i))
+    return out
+
+
+@pytest.mark.parametrize("wl", _random_workloads(36, 7), ids=lambda w: w.name)
+def test_random_shapes_default_planner(wl):
+    # whatever the planner picks for the shape (kernel, work-group size, chunking)
+    x = make_inputs(wl)
+    ref = oracle_reference(wl, x)
+    res = run_gpu(wl, x, fused=True)
+    _check(wl, x, res, *ref, what=repr(wl))
+
+
+@pytest.mark.parametrize("wl", _random_workloads(16, 8), ids=lambda w: w.name)
+def test_random_shapes_single_launch_plan(wl, planner_env):
+    planner_env(SEGKV_TARGET_GROUPS=1)
+    x = make_inputs(wl)
+    ref = oracle_reference(wl, x)
+    res = run_gpu(wl, x, fused=False)
+    _check(wl, x, res, *ref, what=repr(wl))
