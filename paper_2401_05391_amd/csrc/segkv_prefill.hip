@@ -23,26 +23,32 @@
 
 namespace segkv {
 
-constexpr int kPrefillWaves = 4;
-constexpr int kPrefillQueries = kPrefillWaves * kQueryTile;   // query tokens per work-group
+// Waves per work-group (each holds 32 query tokens).  D <= 128: four, two
+// work-groups per CU, so that one group's barrier waits overlap the other's
+// work.  D = 256: eight -- the accumulators leave room for two waves per SIMD
+// only within one work-group's LDS, and K/V tiles are shared by twice the queries.
+constexpr int prefill_waves(int D) { return D <= 128 ? 4 : 8; }
 
 // Two work-groups per CU (two waves per SIMD) for D <= 128, so that one wave's
 // softmax arithmetic overlaps the other's MFMAs.
 template <int D>
-__global__ __launch_bounds__(kPrefillWaves * 64) __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1)))
+__global__ __launch_bounds__(prefill_waves(D) * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void sdpa_prefill_mfma_kernel(PrefillParams p)
 {
     using Geo = MfmaGeometry<D>;
     constexpr int CPR = Geo::CPR, NKS = Geo::NKS, NDB = Geo::NDB;
     constexpr int ROWB = Geo::ROWB, VROWB = Geo::VROWB, TILEB = Geo::TILEB, VTILEB = Geo::VTILEB;
+    constexpr int kPrefillWaves = prefill_waves(D);
+    constexpr int kPrefillQueries = kPrefillWaves * kQueryTile;   // query tokens per work-group
     constexpr int NT = kPrefillWaves * 64;
     constexpr int STAGEB = TILEB + VTILEB;
     constexpr int kVecPerTile = kKeyTile * CPR;            // 16-byte vectors of one operand tile
     constexpr int kVecPerThread = (kVecPerTile + NT - 1) / NT;
     constexpr int OROWB = D * 2 + 16;                      // output staging row pitch
 
-    __shared__ __align__(16) unsigned char s_stage[2][STAGEB];
-    static_assert(2 * STAGEB >= kPrefillWaves * kQueryTile * OROWB, "output staging reuses the tiles");
+    constexpr int OUTB = kPrefillWaves * kQueryTile * OROWB;          // output staging reuses the tiles
+    constexpr int STAGE_PITCH = (2 * STAGEB >= OUTB) ? STAGEB : (OUTB + 1) / 2;
+    __shared__ __align__(16) unsigned char s_stage[2][STAGE_PITCH];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -50,12 +56,16 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
     const int n = lane & 31;
     const int h = lane >> 5;
 
-    // ---- work item: heavy (late) query blocks first ----
+    // ---- work item.  The query blocks of one (request, query head) re-read the
+    // same K/V rows (block j needs keys 0 .. 128 (j+1)), so they are neighbours in
+    // the work order and run on one XCD at about the same time: the re-reads are
+    // served by its L2 instead of HBM.  Within a head the long (late) blocks come
+    // first; heads that share a KV head (grouped queries) are neighbours too. ----
     const int n_qblocks = (p.N0 + kPrefillQueries - 1) / kPrefillQueries;
     int id = xcd_contiguous_index(blockIdx.x, gridDim.x);
-    const int hq = id % p.Hq;                 id /= p.Hq;
-    const int b = id % p.B;                   id /= p.B;
-    const int qblk = n_qblocks - 1 - id;
+    const int qblk = n_qblocks - 1 - id % n_qblocks;   id /= n_qblocks;
+    const int hq = id % p.Hq;                          id /= p.Hq;
+    const int b = id;
     const int g = hq / p.G;
     const int q0 = qblk * kPrefillQueries;
     const int wq0 = q0 + wave * kQueryTile;   // first query token of this wave
@@ -221,14 +231,15 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
 
 hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
 {
-    const int n_qblocks = (p.N0 + kPrefillQueries - 1) / kPrefillQueries;
+    if (D != 64 && D != 128 && D != 256) return hipErrorInvalidValue;
+    const int nw = prefill_waves(D);
+    const int n_qblocks = (p.N0 + nw * kQueryTile - 1) / (nw * kQueryTile);
     const unsigned grid = (unsigned)((size_t)p.B * p.Hq * n_qblocks);
-    const dim3 block(kPrefillWaves * 64);
+    const dim3 block(nw * 64);
     switch (D) {
         case 64:  hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, 0, st, p); break;
         case 128: hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, 0, st, p); break;
-        case 256: hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, 0, st, p); break;
-        default:  return hipErrorInvalidValue;
+        default:  hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, 0, st, p); break;
     }
     return hipGetLastError();
 }
