@@ -127,7 +127,7 @@ Plan make_plan(const segkv_dims* d)
         pl.rchunk = d->T;
         pl.n_pchunks = d->Lp > 0 ? 1 : 0;
         pl.pchunk = d->Lp > 0 ? d->Lp : 1;
-    } else if (d->T <= max_steps_merged) {
+    } else if (pl.mfma && d->T <= max_steps_merged) {
         // Too few units to fill the device, response short enough for one list: cut
         // the unit's rows (prompt rows plus the distinct response rows expected)
         // into equal runs.  The last run takes the tail of the prompt and the whole
@@ -135,7 +135,9 @@ Plan make_plan(const segkv_dims* d)
         long resp_rows = d->beam == 1 ? d->T : (long)d->T + d->T / 8 + 8;
         if (resp_rows > (long)d->T * d->beam) resp_rows = (long)d->T * d->beam;
         const long total = d->Lp + resp_rows;
-        const long want = (target_groups + units - 1) / units;
+        // as many runs as fit the device in one round (one work-group per CU): a few
+        // work-groups left over for a second round would cost a whole run's time
+        const long want = target_groups / units > 1 ? target_groups / units : 1;
         long run = (total + want - 1) / want;
         if (run < min_pchunk) run = min_pchunk;
         run = (run + 31) / 32 * 32;
