@@ -382,6 +382,12 @@ void sdpa_decode_alu_kernel(SdpaParams p)
 // together): out = sum_c acc_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
 // One thread per (query row, 4 consecutive head-dim elements).
 // ---------------------------------------------------------------------------
+// BATCH chunks are combined per pass with every load of the pass in flight at
+// once (first all (m, l) pairs, then all accumulator slices), so a merge of up
+// to BATCH chunks costs two memory round trips.  The launcher picks the smallest
+// BATCH in {4, 8, 16} that covers the chunk count (slots past the last chunk
+// re-read it and are ignored).
+template <int BATCH>
 __global__ __launch_bounds__(256) void sdpa_merge_kernel(_Float16* out, const float* ws_ml,
                                                          const float* ws_acc, int NQ, int D,
                                                          int n_chunks)
@@ -391,30 +397,32 @@ __global__ __launch_bounds__(256) void sdpa_merge_kernel(_Float16* out, const fl
     if (gid >= (size_t)NQ * per_row) return;
     const size_t qidx = gid / per_row;
     const int d4 = (int)(gid % per_row) * 4;
-    // single pass, online: the (m, l) pairs and accumulator slices of four chunks
-    // are requested together so that their latencies overlap
     float mm = kEmptyMax;
     float ll = 0.0f;
     float4_t aa = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int c0 = 0; c0 < n_chunks; c0 += 4) {
-        float2 ml[4];
-        float4_t a[4];
+    for (int c0 = 0; c0 < n_chunks; c0 += BATCH) {
+        float2 ml[BATCH];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < BATCH; ++u) {
             const int ch = min(c0 + u, n_chunks - 1);
             ml[u] = *reinterpret_cast<const float2*>(ws_ml + ((size_t)ch * NQ + qidx) * 2);
+        }
+        float4_t a[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int ch = min(c0 + u, n_chunks - 1);
             a[u] = *reinterpret_cast<const float4_t*>(ws_acc + ((size_t)ch * NQ + qidx) * D + d4);
         }
         float m_new = mm;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < BATCH; ++u)
             if (c0 + u < n_chunks) m_new = fmaxf(m_new, ml[u].x);
         const float corr = fast_exp2(mm - m_new);
         ll *= corr;
         aa *= corr;
         mm = m_new;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < BATCH; ++u) {
             if (c0 + u < n_chunks) {
                 const float f = fast_exp2(ml[u].x - mm);
                 ll += ml[u].y * f;
@@ -521,8 +529,15 @@ hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_
 {
     const size_t threads = (size_t)NQ * (D / 4);
     const unsigned grid = (unsigned)((threads + 255) / 256);
-    hipLaunchKernelGGL(sdpa_merge_kernel, dim3(grid), dim3(256), 0, st, out, ws_ml, ws_acc, NQ, D,
-                       n_chunks);
+    if (n_chunks <= 4)
+        hipLaunchKernelGGL(sdpa_merge_kernel<4>, dim3(grid), dim3(256), 0, st, out, ws_ml, ws_acc, NQ,
+                           D, n_chunks);
+    else if (n_chunks <= 8)
+        hipLaunchKernelGGL(sdpa_merge_kernel<8>, dim3(grid), dim3(256), 0, st, out, ws_ml, ws_acc, NQ,
+                           D, n_chunks);
+    else
+        hipLaunchKernelGGL(sdpa_merge_kernel<16>, dim3(grid), dim3(256), 0, st, out, ws_ml, ws_acc, NQ,
+                           D, n_chunks);
     return hipGetLastError();
 }
 
