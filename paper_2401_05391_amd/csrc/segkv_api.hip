@@ -287,7 +287,9 @@ int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, con
     p.n_rchunks = pl.n_rchunks;
     p.resp_in_last = pl.resp_in_last;
 #ifdef SEGKV_TIMING
-    p.timing = (unsigned long long*)std::getenv("SEGKV_TIMING_PTR") ? (unsigned long long*)std::strtoull(std::getenv("SEGKV_TIMING_PTR"), nullptr, 0) : nullptr;
+    // tuning builds only: device buffer for per-wave phase timestamps, address in the environment
+    const char* timing_ptr = std::getenv("SEGKV_TIMING_PTR");
+    p.timing = timing_ptr ? (unsigned long long*)std::strtoull(timing_ptr, nullptr, 0) : nullptr;
 #endif
 
     hipStream_t st = (hipStream_t)stream;
