@@ -83,7 +83,7 @@ struct DecodeGeometry {
     static_assert(QT == 16 || KT == 32, "the 32-slot shape multiplies 32-key tiles");
 };
 
-template <int D, int NW, int QT>
+template <int D, int NW, int QT, bool SHARED>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void sdpa_decode_mfma_kernel(SdpaParams p)
 {
@@ -121,8 +121,26 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     // Hardware order (group i runs on XCD i % 8): with the KV head as the fastest
     // index each XCD streams one 256-byte column class of every request.  Measured
     // 2% faster on MI355X than giving each XCD a contiguous run of requests.
+    // The query blocks of one unit read the same K/V rows: they get work-group
+    // indices 8 apart, i.e. the same XCD at about the same time, so that the
+    // re-reads are served by that XCD's L2 (and K/V loads are then ordinary, not
+    // non-temporal, loads).
     int id = (int)blockIdx.x;
-    const int qb = id % p.n_qblocks; id /= p.n_qblocks;
+    int qb = 0;
+    if (SHARED) {
+        const int nqb = p.n_qblocks;
+        const int n_units = (int)gridDim.x / nqb;
+        const int full = (n_units / 8) * 8 * nqb;
+        if (id < full) {
+            const int r = id % (8 * nqb);
+            qb = r / 8;
+            id = (id / (8 * nqb)) * 8 + (r % 8);
+        } else {
+            const int r = id - full;
+            qb = r % nqb;
+            id = (n_units / 8) * 8 + r / nqb;
+        }
+    }
     const int g = id % p.Hkv;        id /= p.Hkv;
     const int chunk = id % p.n_chunks;
     const int b = id / p.n_chunks;
@@ -390,12 +408,12 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const uint32_t off = (uint32_t)min(RPI * i + srow, lim) * row_stride + schunk * 8;
-            st.k[i] = load16_stream(kb + off);
+            st.k[i] = SHARED ? load16(kb + off) : load16_stream(kb + off);
         }
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const uint32_t off = (uint32_t)min(RPI * i + srow, lim) * row_stride + schunk * 8;
-            st.v[i] = load16_stream(vb + off);
+            st.v[i] = SHARED ? load16(vb + off) : load16_stream(vb + off);
         }
     };
     auto fetch_dummy = [&](Staged& st) __attribute__((always_inline)) {
@@ -434,8 +452,8 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             const size_t off_old = (((size_t)s * N + b * p.W + slot) * p.Hkv + g) * D + schunk * 8;
             const _Float16* const kp = is_new ? p.k_new + off_new : p.resp_k + off_old;
             const _Float16* const vp = is_new ? p.v_new + off_new : p.resp_v + off_old;
-            st.k[i] = load16_stream(kp);
-            st.v[i] = load16_stream(vp);
+            st.k[i] = SHARED ? load16(kp) : load16_stream(kp);
+            st.v[i] = SHARED ? load16(vp) : load16_stream(vp);
         }
     };
     auto fetch = [&](Staged& st, int ti) __attribute__((always_inline)) {
@@ -571,8 +589,13 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
 template <int D, int NW, int QT>
 static void launch_variant(const SdpaParams& p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT>), dim3(grid), dim3(NW * 64), 0, st,
-                       p);
+    // several query blocks per unit: the variant whose blocks share K/V rows through L2
+    if (p.n_qblocks > 1)
+        hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT, true>), dim3(grid), dim3(NW * 64), 0,
+                           st, p);
+    else
+        hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT, false>), dim3(grid), dim3(NW * 64), 0,
+                           st, p);
 }
 
 hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, int NW, unsigned grid,

@@ -63,6 +63,10 @@ SMALL = [
     Workload("d256_gqa8", B=1, W=4, Hq=16, Hkv=2, D=256, Lp=83, T=21, seed=115),
     Workload("d64_gqa8", B=2, W=4, Hq=8, Hkv=1, D=64, Lp=99, T=27, alibi=True, seed=116),
     Workload("d128_w1_gqa4", B=3, W=1, Hq=8, Hkv=2, D=128, Lp=140, T=20, parents="identity", seed=117),
+    # several query blocks per unit (their work-groups share K/V rows through L2): multi-query
+    # attention with beams, unit counts that are and are not multiples of 8
+    Workload("mqa_w4", B=9, W=4, Hq=24, Hkv=1, D=128, Lp=75, T=19, seed=118),
+    Workload("gqa40_w2", B=4, W=2, Hq=80, Hkv=2, D=64, Lp=60, T=33, alibi=True, seed=119),
 ]
 
 
