@@ -212,8 +212,7 @@ def grow_response(new_k, new_v, old_k, old_v, dims: SegkvDims, stream=None) -> N
                                             int(new_k.shape[0]), ctypes.byref(dims),
                                             _stream_handle(stream))
     if rc != SEGKV_OK:
-        raise SegkvError(rc, "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
-           "segkv_rope_append", "segkv_sdpa_decode_ragged")
+        raise SegkvError(rc, "segkv_grow_response")
 
 
 def stream_read_probe(src, sink, stream=None) -> None:
