@@ -1,9 +1,10 @@
 // libsegkv device code: fused decode-step attention over a segment KV cache
 // (arxiv 2401.05391, Section 3.3) for gfx950, matrix-core (MFMA) path.
 //
-// Used when several queries share every K/V row of a unit (request b, KV head
-// g): the W beams and, under grouped-query attention, the G query heads of the
-// group.  The queries are the N dimension of the MFMAs, a tile of keys is M:
+// The queries that share every K/V row of a unit (request b, KV head g) -- the W
+// beams and, under grouped-query attention, the G query heads of the group; a
+// single query in greedy decode -- are the N dimension of the MFMAs, a tile of
+// keys is M:
 //     S^T[key][query]  = K[key][:]   . Q^T[:][query]       (contraction over D)
 //     O^T[d][query]   += V^T[d][key] . P^T[key][query]     (contraction over keys)
 // so that each K/V row is read from HBM once and reused by all queries.
@@ -11,19 +12,19 @@
 // QT = 16 slots on 16x16x32 / 16x16x16 MFMAs (beam search without grouping: few
 // queries, half the accumulator registers, head dimension up to 256).
 //
-// Each wave streams its own key tiles, with no work-group barrier in the loop:
+// Each wave streams its own key tiles (dealt round-robin), with no work-group
+// barrier in the loop:
 //   global (coalesced 128-bit, non-temporal) -> registers -> wave-private LDS
 //   tile (rows padded by 16 bytes against bank conflicts) -> MFMA operands.
 // While a tile is being multiplied the next one is already in flight in
-// registers.  Softmax statistics are fp32; P is rounded to fp16 for the PV
+// registers.  The last wave first resolves the beam lineage into the list of
+// response rows; the others pick it up when they reach the response tiles.  Softmax statistics are fp32; P is rounded to fp16 for the PV
 // product; the running maximum is only moved when a tile exceeds it by 2^8 so
 // that the accumulator rescale is rare.  Waves are merged through LDS at the end.
 #include "segkv_common.h"
 #include "segkv_launch.h"
 #include "segkv_device.h"
 #include "segkv_mfma_tile.h"
-
-#include <cstdlib>
 
 // Optional phase timestamps for kernel tuning (compiled in only with
 // -DSEGKV_TIMING; slot k of work-group g, wave w lands in p.timing).
