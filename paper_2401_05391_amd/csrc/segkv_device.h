@@ -299,9 +299,9 @@ __device__ __forceinline__ int list_last_window_start(int s0, int s1)
 template <int CAP>
 struct WaveListSmem {
     uint32_t ent[CAP];   // (local step << 16) | (slot << 8) | beam mask
-    int total;
-    int base;            // the list is ent[base .. base + total)
-    int ready;           // set (release) once the three above are final
+    int top;             // ent[top .. CAP) is written; only ever decreases.  The
+                         // kernel sets it to CAP before the builder starts.
+    int ready;           // set (release) once top is final: the list is ent[top .. CAP)
 };
 
 // Called by all 64 lanes of exactly one wave.  Requires (s1 - s0) * W <= CAP and
@@ -317,13 +317,10 @@ __device__ void build_response_list_wave(WaveListSmem<CAP>& sm, const int32_t* p
     const int N = B * W;
     if (W == 1) {
         for (int t = lane; t < n_all; t += 64) {
-            sm.ent[t] = ((uint32_t)t << 16) | 1u;
+            sm.ent[CAP - n_all + t] = ((uint32_t)t << 16) | 1u;
             if (anc_out) anc_out[(size_t)(s0 + t) * N + b] = 0;
         }
-        if (lane == 0) {
-            sm.total = n_all;
-            sm.base = 0;
-        }
+        __hip_atomic_store(&sm.top, CAP - n_all, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         return;
     }
@@ -419,22 +416,30 @@ __device__ void build_response_list_wave(WaveListSmem<CAP>& sm, const int32_t* p
                 }
             }
         }
+        // the window's rows are usable from here on, while the older windows are built
+        __hip_atomic_store(&sm.top, top, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         rows = next_rows;
-    }
-    if (lane == 0) {
-        sm.total = CAP - top;
-        sm.base = top;
     }
     __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-// Any other wave: blocks until the builder wave has published the list (the
-// builder never waits for anything, so this ends).
+// Any other wave: blocks until ent[want .. CAP) is written or the list is final,
+// whichever comes first (the builder never waits for anything, so this ends).
+// Returns the published top and sets `final`.
 template <int CAP>
-__device__ __forceinline__ void wait_response_list(WaveListSmem<CAP>& sm)
+__device__ __forceinline__ int wait_response_list(WaveListSmem<CAP>& sm, int want, bool& final)
 {
-    while (__hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
+    for (;;) {
+        const int rdy = __builtin_amdgcn_readfirstlane(
+            __hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+        const int top = __builtin_amdgcn_readfirstlane(
+            __hip_atomic_load(&sm.top, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+        if (rdy || top <= want) {
+            final = rdy != 0;
+            return top;
+        }
         __builtin_amdgcn_s_sleep(2);
+    }
 }
 
 }  // namespace segkv

@@ -220,7 +220,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         app_v = load16(p.v_new + src);
     }
 
-    const uint32_t* ent = s_list.ent;                  // start of the response list, once it is known
+    const uint32_t* const ent = s_list.ent;
     SEGKV_PHASE_DECL;
     // ---- running state: reference max and partial sum per lane, O^T accumulators ----
     float m_ref = kEmptyMax;
@@ -254,7 +254,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     //   32-slot shape: 8 (r / 4) + 4 h + (r % 4)
     //   16-slot shape: 16 (r / 4) + 4 h + (r % 4)
     auto key_row = [&](int r) { return (WIDE ? 8 : 16) * (r >> 2) + 4 * h + (r & 3); };
-    auto compute_tile = [&](int mode, int base, int total) __attribute__((always_inline)) {
+    auto compute_tile = [&](int mode, int base, int lo) __attribute__((always_inline)) {
         // S^T = K . Q^T
         float s[NSR];
         if constexpr (WIDE) {
@@ -308,10 +308,10 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
 #pragma unroll
             for (int r = 0; r < NSR; ++r) {
                 const int e = base + key_row(r);
-                const uint32_t en = ent[min(e, total - 1)];
+                const uint32_t en = ent[max(e, lo)];
                 const int kpos = Lp + s0 + (int)(en >> 16);
                 const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
-                const bool vis = (e < total) && ((en >> qbeam) & 1u);
+                const bool vis = (e >= lo) && ((en >> qbeam) & 1u);
                 s[r] = vis ? z : -INFINITY;
                 m_tile = fmaxf(m_tile, s[r]);
             }
@@ -424,25 +424,27 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         for (int i = 0; i < NLD; ++i) st.v[i] = load16(dummy);
     };
 
-    // The response list comes from the builder wave; a wave asks for it when it
-    // first reaches a tile past the prompt tiles (by then it is long finished).
-    int total = 0;
-    int n_tiles = n_ptiles;
-    bool list_known = !has_resp;
-    auto need_list = [&]() {
-        if (!list_known) {
-            wait_response_list(s_list);
-            total = s_list.total;
-            ent = s_list.ent + s_list.base;
-            n_tiles = n_ptiles + (total + KT - 1) / KT;
-            list_known = true;
+    // The response list comes from the builder wave, which fills s_list.ent from
+    // the top down, newest window of steps first, and publishes how far it has
+    // got after each window.  Response tile j is ent[LISTCAP - KT (j+1) .. LISTCAP
+    // - KT j): the waves take the tiles of the newest steps while the builder is
+    // still composing the older ones.  Until the list is final the number of
+    // tiles is unknown (n_tiles is an upper bound); a wave asks for tile j just
+    // before it requests that tile's rows.
+    int lo = LISTCAP;                                  // ent[lo .. LISTCAP) is known to be written
+    int n_tiles = has_resp ? (1 << 30) : n_ptiles;
+    bool list_final = !has_resp;
+    auto need_tile = [&](int j) {
+        if (!list_final) {
+            lo = wait_response_list(s_list, LISTCAP - KT * (j + 1), list_final);
+            if (list_final) n_tiles = n_ptiles + (LISTCAP - lo + KT - 1) / KT;
         }
     };
-    auto fetch_response = [&](Staged& st, int ti) __attribute__((always_inline)) {
-        const int base = ti * KT;
+    auto fetch_response = [&](Staged& st, int j) __attribute__((always_inline)) {
+        const int base = LISTCAP - KT * (j + 1);
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const int e = min(base + RPI * i + srow, total - 1);
+            const int e = max(base + RPI * i + srow, lo);
             const uint32_t en = ent[e];
             const int s = s0 + (int)(en >> 16);
             const int slot = (int)((en >> 8) & 0xffu);
@@ -468,7 +470,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             const bool plain = (p.slopes == nullptr) && (base + KT <= k1);
             compute_tile(plain ? 0 : 1, base, 0);
         } else {
-            compute_tile(2, (ti - n_ptiles) * KT, total);
+            compute_tile(2, LISTCAP - KT * (ti - n_ptiles + 1), lo);
         }
     };
 
@@ -477,7 +479,10 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     // keeps the result bit-identical from run to run.)
     Staged st;
     int ti = wave;
-    if (tid == 0) s_list.ready = 0;
+    if (tid == 0) {
+        s_list.ready = 0;
+        s_list.top = LISTCAP;
+    }
     // the first tile needs nothing but addresses when it is a prompt tile
     const bool early = !is_builder && ti < n_ptiles;
     if (early) fetch_prompt(st, ti);
@@ -498,11 +503,11 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     if (is_builder) {
         build_response_list_wave(s_list, p.parent, (g == 0 && qb == 0) ? p.anc_out : nullptr, p.B,
                                  p.W, p.T, b, s0, s1, lrows, lane);
-        need_list();
+        need_tile(0);                                  // final: this wave has just built it
         SEGKV_STAMP(2);
     }
     if (!early) {
-        if (ti >= n_ptiles) need_list();
+        if (ti >= n_ptiles) need_tile(ti - n_ptiles);
         fetch(st, ti);
     }
     SEGKV_PHASE_BEGIN;
@@ -513,7 +518,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         stage_to_lds(st);
         SEGKV_STAMP_FIRST(3);
         const int nxt = ti + NW;
-        if (nxt >= n_ptiles) need_list();
+        if (nxt >= n_ptiles) need_tile(nxt - n_ptiles);
         fetch(st, nxt);
         SEGKV_PHASE(0);
         process(ti);
