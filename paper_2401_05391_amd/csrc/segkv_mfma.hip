@@ -474,11 +474,17 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         }
     };
 
-    // Tiles are dealt round-robin: wave w takes tiles w, w + NW, ...  (Claiming
+    // Tiles are dealt in a fixed order, round-robin over the waves.  (Claiming
     // them from a shared counter measured within 1% of this, and a fixed deal
     // keeps the result bit-identical from run to run.)
     Staged st;
-    int ti = wave;
+    // While the builder wave composes the list the other NW-1 waves deal the
+    // tiles among themselves; it joins the deal after `skip` rounds (a window of
+    // the list costs it about two rounds; measured best among 0 .. 2 per window).
+    const int n_win = (s1 - s0 + kListWindow - 1) / kListWindow;
+    const int skip = (has_resp && p.W > 1) ? 2 * n_win - 1 : 0;
+    const int t_join = skip * (NW - 1);
+    int ti = wave < NW - 1 ? wave : t_join + NW - 1;
     if (tid == 0) {
         s_list.ready = 0;
         s_list.top = LISTCAP;
@@ -517,7 +523,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     while (ti < n_tiles) {
         stage_to_lds(st);
         SEGKV_STAMP_FIRST(3);
-        const int nxt = ti + NW;
+        const int nxt = ti + (ti < t_join ? NW - 1 : NW);
         if (nxt >= n_ptiles) need_tile(nxt - n_ptiles);
         fetch(st, nxt);
         SEGKV_PHASE(0);
