@@ -51,7 +51,7 @@ def algorithmic_bytes(wl, unique_rows: int) -> dict:
 class DeviceSet:
     """One independent set of operands on the GPU (one "layer")."""
 
-    def __init__(self, wl, seed, parent_np, slopes_np, segkv, torch):
+    def __init__(self, wl, seed, parent_np, slopes_np, segkv, torch, prompt_seq_first=False):
         dev = torch.device("cuda:0")
         g = torch.Generator(device=dev)
         g.manual_seed(seed)
@@ -74,8 +74,11 @@ class DeviceSet:
             return v
 
         self.q = rnd(wl.N, wl.Hq, wl.D)
-        self.pk = rnd(wl.B, wl.Lp, wl.Hkv, wl.D)
-        self.pv = staggered(rnd(wl.B, wl.Lp, wl.Hkv, wl.D))
+        # Section 4.1's layout comparison: [Lp, B, Hkv, D] when prompt_seq_first
+        pshape = (wl.Lp, wl.B, wl.Hkv, wl.D) if prompt_seq_first else (wl.B, wl.Lp, wl.Hkv, wl.D)
+        self.prompt_seq_first = prompt_seq_first
+        self.pk = rnd(*pshape)
+        self.pv = staggered(rnd(*pshape))
         self.rk = torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16, device=dev)
         self.rv = staggered(torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16,
                                        device=dev))
@@ -92,7 +95,7 @@ class DeviceSet:
         self.call = segkv.prepare_sdpa_decode(self.out, self.q, self.pk, self.pv, self.rk, self.rv,
                                               self.parent, self.dims, wl.scale, k_new=self.kn,
                                               v_new=self.vn, alibi_slopes=self.slopes,
-                                              workspace=self.ws)
+                                              workspace=self.ws, prompt_seq_first=prompt_seq_first)
 
     def to_numpy(self):
         c = lambda t: None if t is None else t.cpu().numpy()
@@ -107,7 +110,8 @@ def unique_rows_from_anc(anc, wl):
     return int(sum(np.unique(offs + anc[s]).size for s in range(wl.T)))
 
 
-def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_seconds):
+def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_seconds,
+                  prompt_seq_first=False):
     import numpy as np
     from paper_2401_05391_amd.workloads import alibi_slopes, make_parent
 
@@ -118,15 +122,17 @@ def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_second
     row = wl.Hkv * wl.D * 2
     set_bytes = 2 * wl.B * wl.Lp * row + 2 * wl.T * wl.N * row
     n_sets = max(2, math.ceil(4 * MALL_BYTES / set_bytes))
-    sets = [DeviceSet(wl, 1000 * wl.seed + i, parent_np, slopes_np, segkv, torch) for i in range(n_sets)]
+    sets = [DeviceSet(wl, 1000 * wl.seed + i, parent_np, slopes_np, segkv, torch, prompt_seq_first)
+            for i in range(n_sets)]
     torch.cuda.synchronize()
 
     # resolved ancestors as the kernel used them -> distinct response rows referenced
     anc = torch.empty(wl.T, wl.N, dtype=torch.int32, device="cuda:0")
     s0 = sets[0]
     cpu_inputs = s0.to_numpy() if want_cpu_baseline else None
-    segkv.sdpa_decode(s0.out, s0.q, s0.pk, s0.pv, s0.rk, s0.rv, s0.parent, s0.dims, wl.scale,
-                      k_new=s0.kn, v_new=s0.vn, alibi_slopes=s0.slopes, anc_out=anc, workspace=s0.ws)
+    entry = segkv.sdpa_decode_seq_first_prompt if prompt_seq_first else segkv.sdpa_decode
+    entry(s0.out, s0.q, s0.pk, s0.pv, s0.rk, s0.rv, s0.parent, s0.dims, wl.scale,
+          k_new=s0.kn, v_new=s0.vn, alibi_slopes=s0.slopes, anc_out=anc, workspace=s0.ws)
     torch.cuda.synchronize()
     U = unique_rows_from_anc(anc.cpu().numpy(), wl)
     nbytes = algorithmic_bytes(wl, U)
@@ -365,7 +371,12 @@ def main():
         rows = []
         for bs in FIG6_BATCH_SIZES:
             r = time_workload(fig6_workload(bs), a.steps, a.warmup, segkv, torch, False, 0)
+            # the figure's second curve: the prompt segment stored sequence first
+            r2 = time_workload(fig6_workload(bs), a.steps, a.warmup, segkv, torch, False, 0,
+                               prompt_seq_first=True)
             rows.append({"batch_size": bs, "us_per_layer_step": r["us_per_layer_step"],
+                         "seq_first_prompt_device_us_mean": r2["device_us"]["mean"],
+                         "seq_first_prompt_gbs_unique": r2["gbs_unique"],
                          "device_us_mean": r["device_us"]["mean"], "bytes_unique": r["bytes_unique"],
                          "bytes_nominal": r["bytes_nominal"], "gbs_unique": r["gbs_unique"],
                          "gbs_nominal": r["gbs_nominal"], "frac_of_peak": r["roofline"]["frac"],

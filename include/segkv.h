@@ -158,6 +158,28 @@ int segkv_sdpa_decode_ragged(void* out, const void* q,
                              void* workspace, size_t workspace_bytes,
                              float scale, const segkv_dims* d, void* stream);
 
+/*
+ * The same step with the prompt segment stored sequence first, prompt_k /
+ * prompt_v = [Lp, B, Hkv, D] (the response buffers' own layout): the second
+ * arm of the prompt-layout comparison of Section 4.1, which the paper decides
+ * in favour of the batch-first layout that segkv_sdpa_decode takes.  Here for
+ * that comparison and for callers whose prefill writes sequence-first tensors;
+ * every other argument, the arithmetic, the workspace size and the status
+ * codes are those of segkv_sdpa_decode_ragged.  SEGKV_UNSUPPORTED when
+ * B * Hkv * D exceeds 2^25 elements (rows of a tile are addressed with 32-bit
+ * offsets).
+ */
+int segkv_sdpa_decode_seq_first_prompt(void* out, const void* q,
+                                       const void* prompt_k, const void* prompt_v,
+                                       void* resp_k, void* resp_v,
+                                       const int32_t* parent,
+                                       const void* k_new, const void* v_new,
+                                       const float* alibi_slopes,
+                                       const int32_t* prompt_lens,
+                                       int32_t* anc_out,
+                                       void* workspace, size_t workspace_bytes,
+                                       float scale, const segkv_dims* d, void* stream);
+
 /* Bytes of device scratch segkv_sdpa_decode needs for these dimensions (the
  * split-KV partial results of Section 3.3's accumulate step).  0 on invalid
  * dimensions. */

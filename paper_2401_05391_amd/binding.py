@@ -25,7 +25,7 @@ EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_status_string", "segkv_stream_read_probe", "segkv_cache_token_bytes",
            "segkv_cache_standard_bytes", "segkv_cache_segment_bytes", "segkv_response_capacity",
            "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
-           "segkv_rope_append", "segkv_sdpa_decode_ragged")
+           "segkv_rope_append", "segkv_sdpa_decode_ragged", "segkv_sdpa_decode_seq_first_prompt")
 
 
 class SegkvDims(ctypes.Structure):
@@ -63,6 +63,8 @@ def load_library():
     lib.segkv_sdpa_decode_ragged.restype = ctypes.c_int
     lib.segkv_sdpa_decode_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                                              ctypes.c_float, dp, vp]
+    lib.segkv_sdpa_decode_seq_first_prompt.restype = ctypes.c_int
+    lib.segkv_sdpa_decode_seq_first_prompt.argtypes = lib.segkv_sdpa_decode_ragged.argtypes
     lib.segkv_workspace_bytes.restype = sz
     lib.segkv_workspace_bytes.argtypes = [dp]
     lib.segkv_value_stagger_bytes.restype = sz
@@ -162,24 +164,46 @@ def sdpa_decode_ragged(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, promp
         raise SegkvError(rc, "segkv_sdpa_decode_ragged")
 
 
+def sdpa_decode_seq_first_prompt(out, q, prompt_k, prompt_v, resp_k, resp_v, parent,
+                                 dims: SegkvDims, scale: float, k_new=None, v_new=None,
+                                 alibi_slopes=None, prompt_lens=None, anc_out=None, workspace=None,
+                                 stream=None) -> None:
+    """prompt_k / prompt_v are [Lp, B, Hkv, D]; otherwise sdpa_decode_ragged."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load_library().segkv_sdpa_decode_seq_first_prompt(
+        _ptr(out), _ptr(q), _ptr(prompt_k), _ptr(prompt_v), _ptr(resp_k), _ptr(resp_v),
+        _ptr(parent), _ptr(k_new), _ptr(v_new), _ptr(alibi_slopes), _ptr(prompt_lens),
+        _ptr(anc_out), _ptr(workspace), ws_bytes, float(scale), ctypes.byref(dims),
+        _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_sdpa_decode_seq_first_prompt")
+
+
 def prepare_sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvDims,
                         scale: float, k_new=None, v_new=None, alibi_slopes=None, anc_out=None,
-                        workspace=None, stream=None):
+                        workspace=None, stream=None, prompt_seq_first: bool = False):
     """Marshal the arguments once; returns a zero-argument callable that enqueues
     the same segkv_sdpa_decode call each time (for launch loops where per-call
-    Python marshalling would rival the kernel time).  The tensors must stay alive."""
-    fn = load_library().segkv_sdpa_decode
+    Python marshalling would rival the kernel time).  The tensors must stay alive.
+    prompt_seq_first: the prompt tensors are [Lp, B, Hkv, D] and the call is
+    segkv_sdpa_decode_seq_first_prompt."""
+    lib = load_library()
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     vp = ctypes.c_void_p
-    args = ([vp(_ptr(t)) for t in (out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new,
-                                   v_new, alibi_slopes, anc_out, workspace)]
-            + [ctypes.c_size_t(ws_bytes), ctypes.c_float(scale), ctypes.byref(dims),
-               vp(_stream_handle(stream))])
+    head = [vp(_ptr(t)) for t in (out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new,
+                                  v_new, alibi_slopes)]
+    tail = ([vp(_ptr(anc_out)), vp(_ptr(workspace)), ctypes.c_size_t(ws_bytes),
+             ctypes.c_float(scale), ctypes.byref(dims), vp(_stream_handle(stream))])
+    if prompt_seq_first:
+        fn, name, args = (lib.segkv_sdpa_decode_seq_first_prompt,
+                          "segkv_sdpa_decode_seq_first_prompt", head + [vp(None)] + tail)
+    else:
+        fn, name, args = lib.segkv_sdpa_decode, "segkv_sdpa_decode", head + tail
 
     def call() -> None:
         rc = fn(*args)
         if rc != SEGKV_OK:
-            raise SegkvError(rc, "segkv_sdpa_decode")
+            raise SegkvError(rc, name)
     return call
 
 

@@ -237,11 +237,14 @@ int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void
                                     d, stream);
 }
 
-int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, const void* prompt_v,
-                             void* resp_k, void* resp_v, const int32_t* parent, const void* k_new,
-                             const void* v_new, const float* alibi_slopes,
-                             const int32_t* prompt_lens, int32_t* anc_out, void* workspace,
-                             size_t workspace_bytes, float scale, const segkv_dims* d, void* stream)
+namespace {
+
+// prompt_seq_first: prompt_k / prompt_v are [Lp, B, Hkv, D] instead of [B, Lp, Hkv, D]
+int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void* prompt_v,
+                     void* resp_k, void* resp_v, const int32_t* parent, const void* k_new,
+                     const void* v_new, const float* alibi_slopes, const int32_t* prompt_lens,
+                     bool prompt_seq_first, int32_t* anc_out, void* workspace,
+                     size_t workspace_bytes, float scale, const segkv_dims* d, void* stream)
 {
     if (!dims_ok(d)) return SEGKV_INVALID_ARG;
     if (!out || !q || !resp_k || !resp_v) return SEGKV_INVALID_ARG;
@@ -250,6 +253,8 @@ int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, con
     if ((k_new == nullptr) != (v_new == nullptr)) return SEGKV_INVALID_ARG;
     if (!dims_supported(d)) return SEGKV_UNSUPPORTED;
     if ((long)d->B * d->beam * d->Hq > (1L << 28)) return SEGKV_UNSUPPORTED;
+    // a tile's rows are addressed with 32-bit element offsets from the tile's base
+    if (prompt_seq_first && (long)d->B * d->Hkv * d->D > (1L << 25)) return SEGKV_UNSUPPORTED;
     if (misaligned(out) || misaligned(q) || misaligned(resp_k) || misaligned(resp_v) ||
         (d->Lp > 0 && (misaligned(prompt_k) || misaligned(prompt_v))) ||
         (k_new && (misaligned(k_new) || misaligned(v_new))) || misaligned(workspace) ||
@@ -273,6 +278,13 @@ int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, con
     p.v_new = (const _Float16*)v_new;
     p.slopes = alibi_slopes;
     p.prompt_lens = prompt_lens;
+    if (prompt_seq_first) {
+        p.prompt_row_stride = (uint32_t)d->B * d->Hkv * d->D;
+        p.prompt_req_stride = (size_t)d->Hkv * d->D;
+    } else {
+        p.prompt_row_stride = (uint32_t)d->Hkv * d->D;
+        p.prompt_req_stride = (size_t)d->Lp * d->Hkv * d->D;
+    }
     p.anc_out = anc_out;
     p.ws_ml = need ? (float*)workspace : nullptr;
     p.ws_acc = need ? (float*)((char*)workspace + pl.ws_ml_bytes) : nullptr;
@@ -302,6 +314,31 @@ int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, con
         if (e != hipSuccess) return SEGKV_HIP_ERROR;
     }
     return SEGKV_OK;
+}
+
+}  // namespace
+
+int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, const void* prompt_v,
+                             void* resp_k, void* resp_v, const int32_t* parent, const void* k_new,
+                             const void* v_new, const float* alibi_slopes,
+                             const int32_t* prompt_lens, int32_t* anc_out, void* workspace,
+                             size_t workspace_bytes, float scale, const segkv_dims* d, void* stream)
+{
+    return sdpa_decode_impl(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new, v_new,
+                            alibi_slopes, prompt_lens, false, anc_out, workspace, workspace_bytes,
+                            scale, d, stream);
+}
+
+int segkv_sdpa_decode_seq_first_prompt(void* out, const void* q, const void* prompt_k,
+                                       const void* prompt_v, void* resp_k, void* resp_v,
+                                       const int32_t* parent, const void* k_new, const void* v_new,
+                                       const float* alibi_slopes, const int32_t* prompt_lens,
+                                       int32_t* anc_out, void* workspace, size_t workspace_bytes,
+                                       float scale, const segkv_dims* d, void* stream)
+{
+    return sdpa_decode_impl(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new, v_new,
+                            alibi_slopes, prompt_lens, true, anc_out, workspace, workspace_bytes,
+                            scale, d, stream);
 }
 
 int segkv_rope_append(void* q, const void* k_new, const void* v_new, void* resp_k, void* resp_v,

@@ -245,12 +245,13 @@ void sdpa_decode_alu_kernel(SdpaParams p)
     if (k1 > k0) {
         const int n_tiles = (k1 - k0 + TILE - 1) / TILE;
         // (scalar tile base) + (32-bit lane offset): no 64-bit address per load
-        const uint32_t row_stride = (uint32_t)p.Hkv * D;
+        const uint32_t row_stride = p.prompt_row_stride;
         const uint32_t lane_off = (uint32_t)hl * D + c * 8;
         auto fetch = [&](Tile& t, int ti) {
             const int base = k0 + ti * TILE;
             const int lim = min(TILE - 1, k1 - 1 - base);          // last valid row of the tile
-            const size_t tile_off = (((size_t)b * p.Lp + base) * p.Hkv + gb * HP) * D;
+            const size_t tile_off =
+                (size_t)b * p.prompt_req_stride + (size_t)base * row_stride + gb * HP * D;
             const _Float16* const kb = p.prompt_k + tile_off;
             const _Float16* const vb = p.prompt_v + tile_off;
 #pragma unroll

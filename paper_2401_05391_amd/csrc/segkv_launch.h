@@ -31,6 +31,8 @@ struct SdpaParams {
     int pchunk;      // prompt positions per chunk
     int rchunk;      // response steps per chunk (<= kMaxStepsPerChunk)
     int n_rchunks;   // response chunks come first in the chunk index
+    uint32_t prompt_row_stride;   // elements between consecutive keys of one request and head
+    size_t prompt_req_stride;     // elements between the first keys of consecutive requests
     int resp_in_last;   // 1: no response chunks; the last chunk walks its prompt rows and the whole response
 #ifdef SEGKV_TIMING
     unsigned long long* timing;   // tuning builds only: per-wave phase timestamps

@@ -399,11 +399,11 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     // Prompt tiles are addressed as (scalar tile base) + (32-bit lane offset):
     // the lane offsets are the same for every full tile, so no per-load 64-bit
     // address has to be kept in registers.
-    const uint32_t row_stride = (uint32_t)p.Hkv * D;   // elements between consecutive keys
+    const uint32_t row_stride = p.prompt_row_stride;   // elements between consecutive keys
     auto fetch_prompt = [&](Staged& st, int ti) __attribute__((always_inline)) {
         const int base = k0 + ti * KT;
         const int lim = min(KT - 1, k1 - 1 - base);          // last valid row of the tile
-        const size_t tile_off = (((size_t)b * p.Lp + base) * p.Hkv + g) * D;
+        const size_t tile_off = (size_t)b * p.prompt_req_stride + (size_t)base * row_stride + g * D;
         const _Float16* const kb = p.prompt_k + tile_off;
         const _Float16* const vb = p.prompt_v + tile_off;
 #pragma unroll

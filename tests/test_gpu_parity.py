@@ -330,6 +330,55 @@ def test_per_request_prompt_lengths(wl, lens, path, knobs, planner_env):
     assert same_bits(rk.cpu().numpy(), ork) and same_bits(rv.cpu().numpy(), orv)
 
 
+@pytest.mark.parametrize("ragged", [False, True], ids=["equal_lengths", "per_request_lengths"])
+@pytest.mark.parametrize("wl,lens,path,knobs", RAGGED, ids=[c[0].name for c in RAGGED])
+def test_sequence_first_prompt_layout(wl, lens, path, knobs, ragged, planner_env):
+    # Section 4.1's second layout: the prompt segment as [Lp, B, Hkv, D].  Same
+    # values, same order of arithmetic -> the same bits as the batch-first call,
+    # and parity with the oracle (which only knows the batch-first tensors).
+    import torch
+    import paper_2401_05391_amd as segkv
+    from oracle import segkv_oracle as oracle
+    planner_env(SEGKV_PATH=path, **knobs)
+    x = make_inputs(wl)
+    lens = np.asarray(lens if ragged else [wl.Lp] * wl.B, dtype=np.int32)
+    for b, lb in enumerate(lens):
+        x["prompt_k"][b, lb:] = np.float16(np.nan)
+        x["prompt_v"][b, lb:] = np.float16(np.nan)
+    dev = torch.device("cuda:0")
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+    nbytes = segkv.workspace_bytes(dims)
+    outs = []
+    for seq_first in (False, True):
+        pk, pv = up(x["prompt_k"]), up(x["prompt_v"])
+        if seq_first:
+            pk, pv = pk.transpose(0, 1).contiguous(), pv.transpose(0, 1).contiguous()
+            assert pk.shape == (wl.Lp, wl.B, wl.Hkv, wl.D)
+        rk, rv = up(x["resp_k"]), up(x["resp_v"])
+        ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=dev) if nbytes else None
+        out = torch.full((wl.N, wl.Hq, wl.D), float("nan"), dtype=torch.float16, device=dev)
+        anc = torch.full((wl.T, wl.N), -1, dtype=torch.int32, device=dev)
+        kw = dict(k_new=up(x["k_new"]), v_new=up(x["v_new"]), alibi_slopes=up(x["slopes"]), anc_out=anc,
+                  workspace=ws)
+        if seq_first:
+            segkv.sdpa_decode_seq_first_prompt(out, up(x["q"]), pk, pv, rk, rv, up(x["parent"]), dims, wl.scale,
+                                               prompt_lens=up(lens) if ragged else None, **kw)
+        else:
+            segkv.sdpa_decode_ragged(out, up(x["q"]), pk, pv, rk, rv, up(x["parent"]), up(lens), dims, wl.scale, **kw)
+        torch.cuda.synchronize()
+        outs.append((out.cpu().numpy(), anc.cpu().numpy(), rk.cpu().numpy(), rv.cpu().numpy()))
+    ork, orv = x["resp_k"].copy(), x["resp_v"].copy()
+    oracle.append_kv(ork, orv, x["k_new"], x["v_new"], wl.T - 1)
+    ref, ref_anc = oracle.sdpa_decode_ragged(x["q"], x["prompt_k"], x["prompt_v"], ork, orv, x["parent"],
+                                             wl.W, wl.T, wl.scale, lens, slopes=x["slopes"])
+    got, got_anc, got_rk, got_rv = outs[1]
+    assert np.array_equal(got_anc, ref_anc)
+    assert_parity(got, ref, wl.name)
+    assert same_bits(got_rk, ork) and same_bits(got_rv, orv)
+    assert same_bits(got, outs[0][0]), "the two prompt layouts must give the same bits"
+
+
 def _random_workloads(n, seed):
     """Seeded draw of small shapes across every dimension the planner looks at."""
     rng = np.random.default_rng(seed)
