@@ -316,15 +316,12 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
                 m_tile = fmaxf(m_tile, s[r]);
             }
         }
-        // the lanes that share this lane's query
-        if constexpr (WIDE) {
-            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
-        } else {
-            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16));
-            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
-        }
-        // move the reference maximum only when a tile exceeds it by the slack
+        // Move the reference maximum only when a tile exceeds it by the slack.  The
+        // lanes that share a query hold different keys, but the vote is wave-wide, so
+        // their maxima need to be exchanged only when the reference does move.
         if (__any(m_tile > m_ref + kRescaleSlack)) {
+            if constexpr (!WIDE) m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16));
+            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
             const float m_new = fmaxf(m_ref, m_tile);
             const float corr = fast_exp2(m_ref - m_new);
             m_ref = m_new;

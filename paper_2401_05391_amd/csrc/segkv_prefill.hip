@@ -37,7 +37,11 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
 {
     using Geo = MfmaGeometry<D>;
     constexpr int CPR = Geo::CPR, NKS = Geo::NKS, NDB = Geo::NDB;
-    constexpr int ROWB = Geo::ROWB, VROWB = Geo::VROWB, TILEB = Geo::TILEB, VTILEB = Geo::VTILEB;
+    constexpr int ROWB = Geo::ROWB, TILEB = Geo::TILEB;
+    // V rows 32 bytes apart modulo 256: the four rows of a transposing read (32
+    // bytes each) fall into different banks.  (4-8% over the decode kernel's
+    // pitch here, where LDS reads are half of the CU's busy cycles.)
+    constexpr int VROWB = D * 2 + 32, VTILEB = kKeyTile * VROWB;
     constexpr int kPrefillWaves = prefill_waves(D);
     constexpr int kPrefillQueries = kPrefillWaves * kQueryTile;   // query tokens per work-group
     constexpr int NT = kPrefillWaves * 64;
@@ -154,8 +158,10 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
                 m_tile = fmaxf(m_tile, s[r]);
             }
         }
-        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+        // The two lanes that share a query (keys 4h..) see different keys, but the
+        // vote is wave-wide: their maxima are only exchanged when the reference moves.
         if (__any(m_tile > m_ref + kRescaleSlack)) {
+            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
             const float m_new = fmaxf(m_ref, m_tile);
             const float corr = fast_exp2(m_ref - m_new);
             m_ref = m_new;
