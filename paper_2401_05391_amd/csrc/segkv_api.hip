@@ -44,20 +44,18 @@ bool dims_supported(const segkv_dims* d)
     return (d->D == 64 || d->D == 128 || d->D == 256) && d->beam <= 8;
 }
 
-// Which kernel.  The matrix-core kernel whenever several queries share each K/V
-// row (beams and/or grouped query heads): measured faster than the vector-ALU
-// kernel from 2 queries up at every batch size.  With a single query per row
-// (greedy decode without grouping) it still wins once there are enough
-// (request, KV head) units to keep every CU supplied with whole units (>= 1024:
-// 82% against 80% of peak on the Llama2-7B shape); below that the vector-ALU
-// kernel's finer work items fill the device better.  SEGKV_PATH=alu|mfma
-// overrides (A/B measurements and tests).
-bool want_mfma(int nq, long kv_units)
+// Which kernel.  The matrix-core kernel, always: its tile stream (one tile in
+// flight per wave, operands through LDS) is HBM-bound from a single query per
+// K/V row up, and measured faster than the vector-ALU kernel at every shape
+// tried, greedy decode included (Llama2-7B shape, one query per row: 10.9
+// against 14.9 us at batch 1, 27 against 31 us at batch 8, 90 against 98 us at
+// batch 31; the one exception found, D = 256 with one query per row and 128
+// units, is 5% the other way).  The vector-ALU kernel stays in the library as
+// the second implementation the tests compare: SEGKV_PATH=alu selects it.
+bool want_mfma(int /*nq*/, long /*kv_units*/)
 {
     const char* s = std::getenv("SEGKV_PATH");
-    if (s && s[0] == 'a') return false;
-    if (s && s[0] == 'm') return true;
-    return nq >= 2 || kv_units >= 1024;
+    return !(s && s[0] == 'a');
 }
 
 // How the keys of one (request, KV head) unit are cut into work-groups.
