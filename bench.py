@@ -324,6 +324,55 @@ def run_counter_calibration(segkv, torch):
             "stream_read_probe_kernel": {"bytes_read": 1 << 30, "bytes_written": 4096 * 4}}
 
 
+def graph_bench(layers, steps, warmup, segkv, torch):
+    """Small batches are launch-bound: `layers` decode layer-steps (each on its own
+    K/V buffers, as the layers of a model) launched one by one from Python against
+    the same launches replayed from one HIP graph."""
+    import numpy as np
+    from paper_2401_05391_amd.workloads import alibi_slopes, fig6_workload, make_parent
+    rows = []
+    for bs in (1, 2, 4, 16):
+        wl = fig6_workload(bs)
+        parent_np = make_parent(wl, np.random.default_rng(wl.seed))
+        sets = [DeviceSet(wl, 1000 * wl.seed + i, parent_np, None, segkv, torch) for i in range(layers)]
+        torch.cuda.synchronize()
+
+        def token_step():
+            for s in sets:
+                s.call()
+
+        # the prepared calls above are bound to the stream that was current when
+        # they were made; the recorded ones must go to the capturing stream
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for s in sets:
+                segkv.prepare_sdpa_decode(s.out, s.q, s.pk, s.pv, s.rk, s.rv, s.parent, s.dims, wl.scale,
+                                          k_new=s.kn, v_new=s.vn, workspace=s.ws)()
+        torch.cuda.synchronize()
+        res = {}
+        for name, fn in (("eager", token_step), ("graph", graph.replay)):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            res[name] = (time.perf_counter() - t0) / (steps * layers) * 1e6
+        rows.append({"batch_size": bs, "eager_us_per_layer_step": res["eager"],
+                     "graph_us_per_layer_step": res["graph"]})
+    last = rows[0]
+    return {"metric": "fused segment-KV decode SDPA: us per layer-step, launches replayed from one HIP graph",
+            "value": last["graph_us_per_layer_step"], "unit": "us", "n_gpus": 1, "steps": steps,
+            "warmup": warmup, "ms_per_step": last["graph_us_per_layer_step"] * layers * 1e-3,
+            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+            "data": "synthetic",
+            "config": {"workload": "fig6_llama2_13b_graph", "beam": 4, "Hq": 40, "Hkv": 40, "D": 128,
+                       "Lp": 1024, "T": 128, "layers_per_graph": layers,
+                       "value_is_batch_size": last["batch_size"]},
+            "sweep": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -343,6 +392,10 @@ def main():
                     help="instead of the decode step, time segkv_sdpa_prefill (causal prompt attention, "
                          "the step that writes the prompt segment) on the shapes of the benchmark "
                          "models and print one JSON line with an MFMA roofline")
+    ap.add_argument("--graph", type=int, default=0, metavar="LAYERS",
+                    help="instead of the headline workload, time LAYERS decode layer-steps per token "
+                         "(Figure 6 shape, small batches) launched one by one and replayed from one "
+                         "HIP graph, and print one JSON line")
     ap.add_argument("--calibrate-counters", action="store_true",
                     help="also launch a plain copy of known size (segkv_append_kv, 2 x 128 MiB read and "
                          "written) and a plain read of known size (segkv_stream_read_probe, 1 GiB), "
@@ -364,6 +417,10 @@ def main():
 
     if a.prefill:
         print(json.dumps(prefill_bench(a.steps, a.warmup, segkv, torch)), flush=True)
+        return
+
+    if a.graph:
+        print(json.dumps(graph_bench(a.graph, a.steps, a.warmup, segkv, torch)), flush=True)
         return
 
     if a.fig6_sweep:
