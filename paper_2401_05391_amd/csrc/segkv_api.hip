@@ -252,6 +252,7 @@ int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void*
     if (!dims_supported(d)) return SEGKV_UNSUPPORTED;
     if ((long)d->B * d->beam * d->Hq > (1L << 28)) return SEGKV_UNSUPPORTED;
     // a tile's rows are addressed with 32-bit element offsets from the tile's base
+    if ((long)d->Hkv * d->D > (1L << 25)) return SEGKV_UNSUPPORTED;
     if (prompt_seq_first && (long)d->B * d->Hkv * d->D > (1L << 25)) return SEGKV_UNSUPPORTED;
     if (misaligned(out) || misaligned(q) || misaligned(resp_k) || misaligned(resp_v) ||
         (d->Lp > 0 && (misaligned(prompt_k) || misaligned(prompt_v))) ||
