@@ -15,7 +15,10 @@
 // keys are staged once per work-group into double-buffered LDS (one barrier
 // per tile) and read by all four waves; the V^T operand comes out of LDS with
 // the transposing read.  Later query blocks have more keys to visit, so they
-// are scheduled first.
+// are scheduled first.  Two kernels: sdpa_prefill_mfma_kernel<D> stages the
+// tiles through registers (D = 64, 256); sdpa_prefill_direct_kernel (D = 128)
+// copies them from global memory straight into LDS, three tiles deep.
+#include <cstdlib>
 #include "segkv_common.h"
 #include "segkv_launch.h"
 #include "segkv_device.h"
@@ -235,6 +238,221 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
     }
 }
 
+// ---------------------------------------------------------------------------
+// D = 128 variant whose K/V tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4: lane i's 16 bytes land at base + 16 i, no registers
+// and no LDS store instructions in between), three tiles deep.
+//
+// A copy instruction fills 1 KB = 4 whole rows without padding, so rows are 256
+// bytes apart and bank conflicts are avoided by permuting the 16-byte chunks of
+// a row instead: the lane that fills position c' of row r fetches chunk
+//     K tile:  c = c' ^ (r & 15)                 (16 consecutive rows reading one
+//                                                 chunk hit 16 different positions)
+//     V tile:  c = (((c' >> 1) ^ (r & 7)) << 1) | (c' & 1)
+//                                                (the 4 rows of a transposing read,
+//                                                 32 bytes each, hit 4 different ones)
+// and the operand reads apply the same permutation.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void copy16_to_lds(const _Float16* gptr, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_base)
+                 : "memory");
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void sdpa_prefill_direct_kernel(PrefillParams p)
+{
+    constexpr int D = 128;
+    constexpr int CPR = D / 8, NKS = D / 16, NDB = D / 32;
+    constexpr int ROWB = D * 2;                            // no padding: see above
+    constexpr int TILEB = kKeyTile * ROWB, STAGEB = 2 * TILEB, NSTAGE = 3;
+    constexpr int RPI = 64 / CPR;                          // rows per copy instruction
+    constexpr int NINS = kKeyTile / RPI;                   // copy instructions per operand tile
+    constexpr int NWAVES = 4, INS_PER_WAVE = NINS / NWAVES;
+    constexpr int kQueries = NWAVES * kQueryTile;
+    constexpr int OROWB = D * 2 + 16;
+    static_assert(NWAVES * kQueryTile * OROWB <= NSTAGE * STAGEB, "output staging reuses the tiles");
+    __shared__ __align__(256) unsigned char s_stage[NSTAGE * STAGEB];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31;
+    const int h = lane >> 5;
+
+    const int n_qblocks = (p.N0 + kQueries - 1) / kQueries;
+    int id = xcd_contiguous_index(blockIdx.x, gridDim.x);
+    const int qblk = n_qblocks - 1 - id % n_qblocks;   id /= n_qblocks;
+    const int hq = id % p.Hq;                          id /= p.Hq;
+    const int b = id;
+    const int g = hq / p.G;
+    const int q0 = qblk * kQueries;
+    const int wq0 = q0 + wave * kQueryTile;
+    const int qi = wq0 + n;
+    const float slope2 = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
+
+    // ---- tile copies: this wave's share is INS_PER_WAVE instructions per operand ----
+    const int k_end = min(q0 + kQueries, p.N0);
+    const int n_tiles = (k_end + kKeyTile - 1) / kKeyTile;
+    const uint32_t row_stride = (uint32_t)p.Hkv * D;
+    const unsigned lds0 =
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)s_stage;
+    const int crow = lane / CPR;                          // row within the instruction's 4
+    const int cpos = lane % CPR;                          // chunk position filled by this lane
+    auto issue = [&](int ti, int stage) __attribute__((always_inline)) {
+        const int base = ti * kKeyTile;
+        const int lim = min(kKeyTile - 1, p.N0 - 1 - base);
+        const size_t tile_off = (((size_t)b * p.N0 + base) * p.Hkv + g) * D;
+        const unsigned sbase = lds0 + stage * STAGEB;
+#pragma unroll
+        for (int j = 0; j < INS_PER_WAVE; ++j) {
+            const int i = wave * INS_PER_WAVE + j;
+            const int r = RPI * i + crow;
+            const uint32_t roff = (uint32_t)min(r, lim) * row_stride;
+            const int ck = cpos ^ (r & (CPR - 1));
+            const int cv = (((cpos >> 1) ^ (r & 7)) << 1) | (cpos & 1);
+            copy16_to_lds(p.k + tile_off + roff + ck * 8, sbase + i * 1024);
+            copy16_to_lds(p.v + tile_off + roff + cv * 8, sbase + TILEB + i * 1024);
+        }
+    };
+    issue(0, 0);
+    if (n_tiles > 1) issue(1, 1);
+
+    // ---- Q^T operand in registers ----
+    half8_t qreg[NKS];
+    {
+        const int qrow = min(qi, p.N0 - 1);
+        const _Float16* qp = p.q + (((size_t)b * p.N0 + qrow) * p.Hq + hq) * D;
+#pragma unroll
+        for (int t = 0; t < NKS; ++t)
+            qreg[t] = __builtin_bit_cast(half8_t, load16(qp + 16 * t + 8 * h));
+        // The compiler's wait for these loads must sit here and not inside the tile
+        // loop, where it would also wait for the tile copies in flight (which it
+        // does not know of).
+#pragma unroll
+        for (int t = 0; t < NKS; ++t) asm volatile("" : "+v"(qreg[t]));
+    }
+
+    float m_ref = kEmptyMax;
+    float l_part = 0.0f;
+    float16_t o_acc[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.0f;
+
+    const int grp = lane >> 4;
+    const int li = lane & 15;
+    const int kx = (n & (CPR - 1)) << 4;                               // K chunk permutation of row n
+    const int vrow = 4 * h + (li >> 2);                                // first V row of this lane
+    const int vy = ((grp & 1) ^ (vrow & 7)) << 5;                      // V pair permutation
+    const int tr_base = vrow * ROWB + 8 * (li & 3);
+
+    auto compute_tile = [&](const unsigned char* k_tile, const unsigned char* v_tile, int base,
+                            bool diagonal) __attribute__((always_inline)) {
+        float16_t s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < NKS; ++t) {
+            const half8_t a =
+                *reinterpret_cast<const half8_t*>(k_tile + n * ROWB + (((2 * t + h) << 4) ^ kx));
+            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
+        }
+        float m_tile = -INFINITY;
+        if (!diagonal && p.slopes == nullptr) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                s[r] *= p.scale2;
+                m_tile = fmaxf(m_tile, s[r]);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = base + 8 * (r >> 2) + 4 * h + (r & 3);
+                const float z = s[r] * p.scale2 + slope2 * (float)(key - qi);
+                s[r] = (key <= qi) ? z : -INFINITY;
+                m_tile = fmaxf(m_tile, s[r]);
+            }
+        }
+        if (__any(m_tile > m_ref + kRescaleSlack)) {
+            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+            const float m_new = fmaxf(m_ref, m_tile);
+            const float corr = fast_exp2(m_ref - m_new);
+            m_ref = m_new;
+            l_part *= corr;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[db][r] *= corr;
+        }
+        half8_t pb[2];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float pr = fast_exp2(s[r] - m_ref);
+            l_part += pr;
+            pb[r >> 3][r & 7] = (_Float16)pr;
+        }
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int off = tr_base + (16 * u) * ROWB + ((db * 64) ^ vy);
+                const half4_t lo = lds_read_tr16(v_tile + off);
+                const half4_t hi = lds_read_tr16(v_tile + off + 8 * ROWB);
+                const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- main loop: tile ti is computed while ti+1 and ti+2 are on their way.
+    // s_waitcnt immediates: vmcnt in bits 3:0, no wait on the other counters. ----
+    int stage = 0;
+    for (int ti = 0; ti < n_tiles; ++ti) {
+        // this wave's copies of tile ti have landed (the 2 * INS_PER_WAVE newest belong to ti+1)
+        if (ti + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * INS_PER_WAVE));
+        else                  __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();      // everybody's have; and everybody is done with tile ti-1's stage
+        if (ti + 2 < n_tiles) issue(ti + 2, stage == 0 ? 2 : stage - 1);
+        const int base = ti * kKeyTile;
+        if (base <= wq0 + kQueryTile - 1) {
+            const unsigned char* const k_tile = s_stage + stage * STAGEB;
+            compute_tile(k_tile, k_tile + TILEB, base, base + kKeyTile - 1 > wq0);
+        }
+        stage = stage == NSTAGE - 1 ? 0 : stage + 1;
+    }
+    __syncthreads();
+
+    // ---- normalise, transpose through LDS, store rows with 128-bit writes ----
+    l_part += __shfl_xor(l_part, 32);
+    const float inv = 1.0f / l_part;
+    unsigned char* const obuf = s_stage + wave * (kQueryTile * OROWB);
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            half4_t o4;
+            o4.x = (_Float16)(o_acc[db][4 * i + 0] * inv);
+            o4.y = (_Float16)(o_acc[db][4 * i + 1] * inv);
+            o4.z = (_Float16)(o_acc[db][4 * i + 2] * inv);
+            o4.w = (_Float16)(o_acc[db][4 * i + 3] * inv);
+            *reinterpret_cast<half4_t*>(obuf + n * OROWB + ((32 * db + 8 * i + 4 * h) << 1)) = o4;
+        }
+    constexpr int kRowsPerPass = 64 / CPR;
+#pragma unroll
+    for (int r0 = 0; r0 < kQueryTile; r0 += kRowsPerPass) {
+        const int row = r0 + lane / CPR;
+        const int ch = lane % CPR;
+        const int tok = wq0 + row;
+        const u32x4_t w = *reinterpret_cast<const u32x4_t*>(obuf + row * OROWB + (ch << 4));
+        if (tok < p.N0)
+            store16(p.out + (((size_t)b * p.N0 + tok) * p.Hq + hq) * D + ch * 8, w);
+    }
+}
+
 hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
 {
     if (D != 64 && D != 128 && D != 256) return hipErrorInvalidValue;
@@ -242,9 +460,15 @@ hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
     const int n_qblocks = (p.N0 + nw * kQueryTile - 1) / (nw * kQueryTile);
     const unsigned grid = (unsigned)((size_t)p.B * p.Hq * n_qblocks);
     const dim3 block(nw * 64);
+    // SEGKV_PREFILL=regs keeps the register-staged kernel at D = 128 (A/B measurements, tests)
+    const char* env = std::getenv("SEGKV_PREFILL");
+    const bool direct = D == 128 && !(env && env[0] == 'r');
     switch (D) {
         case 64:  hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, 0, st, p); break;
-        case 128: hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, 0, st, p); break;
+        case 128:
+            if (direct) hipLaunchKernelGGL(sdpa_prefill_direct_kernel, dim3(grid), block, 0, st, p);
+            else hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, 0, st, p);
+            break;
         default:  hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, 0, st, p); break;
     }
     return hipGetLastError();

@@ -41,9 +41,15 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("staging", ["direct", "regs"])
 @pytest.mark.parametrize("B,N0,Hq,Hkv,D,alibi", CASES)
-def test_prefill_matches_oracle(B, N0, Hq, Hkv, D, alibi):
+def test_prefill_matches_oracle(B, N0, Hq, Hkv, D, alibi, staging, monkeypatch):
+    # D = 128 has two kernels: tiles copied straight into LDS (the default) and
+    # tiles staged through registers (SEGKV_PREFILL=regs); other D ignore the knob
     from oracle import segkv_oracle as oracle
+    if staging == "regs" and D != 128:
+        pytest.skip("one kernel only at this head dimension")
+    monkeypatch.setenv("SEGKV_PREFILL", staging)
     print(f"\n[case] prefill B={B} N0={N0} Hq={Hq} Hkv={Hkv} D={D} alibi={alibi}", flush=True)
     q, k, v = _draw(B, N0, Hq, Hkv, D, 1000 + N0)
     slopes = alibi_slopes(Hq) if alibi else None
