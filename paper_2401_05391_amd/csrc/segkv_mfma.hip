@@ -18,9 +18,12 @@
 //   tile (rows padded by 16 bytes against bank conflicts) -> MFMA operands.
 // While a tile is being multiplied the next one is already in flight in
 // registers.  The last wave first resolves the beam lineage into the list of
-// response rows; the others pick it up when they reach the response tiles.  Softmax statistics are fp32; P is rounded to fp16 for the PV
-// product; the running maximum is only moved when a tile exceeds it by 2^8 so
-// that the accumulator rescale is rare.  Waves are merged through LDS at the end.
+// response rows, newest steps first, publishing it window by window; the
+// others take the response tiles from the newest end as they become available,
+// and deal the first rounds of tiles among themselves while the builder is
+// busy.  Softmax statistics are fp32; P is rounded to fp16 for the PV product;
+// the running maximum is only moved when a tile exceeds it by 2^8 so that the
+// accumulator rescale is rare.  Waves are merged through LDS at the end.
 #include "segkv_common.h"
 #include "segkv_launch.h"
 #include "segkv_device.h"
