@@ -51,7 +51,8 @@ def algorithmic_bytes(wl, unique_rows: int) -> dict:
 class DeviceSet:
     """One independent set of operands on the GPU (one "layer")."""
 
-    def __init__(self, wl, seed, parent_np, slopes_np, segkv, torch, prompt_seq_first=False):
+    def __init__(self, wl, seed, parent_np, slopes_np, segkv, torch, prompt_seq_first=False,
+                 lineage=None, lineage_capacity=0):
         dev = torch.device("cuda:0")
         g = torch.Generator(device=dev)
         g.manual_seed(seed)
@@ -95,7 +96,8 @@ class DeviceSet:
         self.call = segkv.prepare_sdpa_decode(self.out, self.q, self.pk, self.pv, self.rk, self.rv,
                                               self.parent, self.dims, wl.scale, k_new=self.kn,
                                               v_new=self.vn, alibi_slopes=self.slopes,
-                                              workspace=self.ws, prompt_seq_first=prompt_seq_first)
+                                              workspace=self.ws, prompt_seq_first=prompt_seq_first,
+                                              lineage=lineage, lineage_capacity=lineage_capacity)
 
     def to_numpy(self):
         c = lambda t: None if t is None else t.cpu().numpy()
@@ -110,8 +112,21 @@ def unique_rows_from_anc(anc, wl):
     return int(sum(np.unique(offs + anc[s]).size for s in range(wl.T)))
 
 
+def build_lineage(wl, parent_np, segkv, torch):
+    """The lineage list after wl.T steps: one segkv_lineage_update per step, as a
+    generation loop would have issued them (once per token, shared by all layers)."""
+    cap = ((wl.Tcap * wl.W + 3) // 4) * 4
+    dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+    buf = torch.zeros(segkv.lineage_bytes(dims, cap) // 4, dtype=torch.int32, device="cuda:0")
+    rows = torch.from_numpy(parent_np).to("cuda:0")
+    for t in range(wl.T):
+        segkv.lineage_update(buf, cap, rows[t] if t > 0 else None, t, dims)
+    torch.cuda.synchronize()
+    return buf, cap
+
+
 def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_seconds,
-                  prompt_seq_first=False):
+                  prompt_seq_first=False, use_lineage=False):
     import numpy as np
     from paper_2401_05391_amd.workloads import alibi_slopes, make_parent
 
@@ -122,7 +137,9 @@ def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_second
     row = wl.Hkv * wl.D * 2
     set_bytes = 2 * wl.B * wl.Lp * row + 2 * wl.T * wl.N * row
     n_sets = max(2, math.ceil(4 * MALL_BYTES / set_bytes))
-    sets = [DeviceSet(wl, 1000 * wl.seed + i, parent_np, slopes_np, segkv, torch, prompt_seq_first)
+    lin, lin_cap = build_lineage(wl, parent_np, segkv, torch) if use_lineage else (None, 0)
+    sets = [DeviceSet(wl, 1000 * wl.seed + i, parent_np, slopes_np, segkv, torch, prompt_seq_first,
+                      lin, lin_cap)
             for i in range(n_sets)]
     torch.cuda.synchronize()
 
@@ -396,6 +413,9 @@ def main():
                     help="instead of the headline workload, time LAYERS decode layer-steps per token "
                          "(Figure 6 shape, small batches) launched one by one and replayed from one "
                          "HIP graph, and print one JSON line")
+    ap.add_argument("--lineage", action="store_true",
+                    help="time segkv_sdpa_decode_lineage (the list of response rows kept across steps by "
+                         "segkv_lineage_update) instead of segkv_sdpa_decode (raw parent table)")
     ap.add_argument("--calibrate-counters", action="store_true",
                     help="also launch a plain copy of known size (segkv_append_kv, 2 x 128 MiB read and "
                          "written) and a plain read of known size (segkv_stream_read_probe, 1 GiB), "
@@ -451,10 +471,12 @@ def main():
         return
 
     wl = CONFIGS[a.workload]
-    main_res = time_workload(wl, a.steps, a.warmup, segkv, torch, not a.no_cpu_baseline, a.cpu_seconds)
+    main_res = time_workload(wl, a.steps, a.warmup, segkv, torch, not a.no_cpu_baseline, a.cpu_seconds,
+                             use_lineage=a.lineage)
     others = []
     for name in [n for n in a.others.split(",") if n and n != a.workload]:
-        others.append(time_workload(CONFIGS[name], a.steps, a.warmup, segkv, torch, False, 0))
+        others.append(time_workload(CONFIGS[name], a.steps, a.warmup, segkv, torch, False, 0,
+                                    use_lineage=a.lineage))
 
     calibration = None
     if a.calibrate_counters:
@@ -468,6 +490,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": wl.name, **main_res["shape"], "append": "fused",
+                   "beam_lineage": "list kept across steps" if a.lineage else "parent table",
                    "buffer_sets": main_res["buffer_sets"]},
         "pct_of_hbm_peak": 100.0 * main_res["gbs_unique"] / HBM_PEAK_GBS,
         "roofline": main_res["roofline"],

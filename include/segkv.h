@@ -180,6 +180,53 @@ int segkv_sdpa_decode_seq_first_prompt(void* out, const void* q,
                                        void* workspace, size_t workspace_bytes,
                                        float scale, const segkv_dims* d, void* stream);
 
+/*
+ * The lineage list: the index tensor of Section 3.3 (which response row every
+ * beam reads at every past step; the paper obtains it once per generated token,
+ * as FasterTransformer does) kept with equal rows merged.  Per request one
+ * entry (step << 16) | (slot << 8) | mask for every distinct (step, slot) row
+ * that some beam of the request still descends from; mask bit j = beam j reads
+ * it; ordered by step, and by slot within a step.  With it the attention call
+ * of every layer reads the list instead of re-deriving it from the parent table
+ * (which costs one wave 3.5-5 us per 256 steps in every work-group: nothing next
+ * to a long prompt, a third of the time when the response is the longer part).
+ *
+ *   lineage            device buffer of segkv_lineage_bytes(d, lineage_capacity)
+ *                      bytes, 16-byte aligned, owned by the caller, opaque
+ *                      (per request a 4-word header, then the entries).  No
+ *                      initialisation is needed: the call with t == 0 starts
+ *                      every request's list.
+ *   lineage_capacity   entries per request: a multiple of 4, at least beam times
+ *                      the number of steps the list will ever hold.
+ *
+ * segkv_lineage_update   one generated token, all requests, one small launch:
+ *   must be called for t = 0, 1, 2, ... in order, once per step (NOT per layer).
+ *   parent_row = row t of the parent table ([B*beam] int32, as in
+ *   segkv_sdpa_decode: parent_row[b*beam+j] is the slot at step t-1 of the
+ *   hypothesis that slot j extends at step t); ignored, and may be NULL, for
+ *   t == 0 and for beam == 1.  Old entries keep the beams whose parent was among
+ *   their readers and are dropped when none was; step t adds one row per beam.
+ *   Uses d->B and d->beam; 0 <= t < 65536.
+ *
+ * segkv_sdpa_decode_lineage   segkv_sdpa_decode_ragged with the list in place of
+ *   the parent table (prompt_lens may be NULL).  The list must have been updated
+ *   through step d->T - 1.  Same arithmetic in the same order: the output is
+ *   bit-identical to the call with the raw table.  No anc_out.  The workspace is
+ *   that of segkv_sdpa_decode.
+ */
+size_t segkv_lineage_bytes(const segkv_dims* d, int32_t lineage_capacity);
+int segkv_lineage_update(void* lineage, int32_t lineage_capacity, const int32_t* parent_row,
+                         int32_t t, const segkv_dims* d, void* stream);
+int segkv_sdpa_decode_lineage(void* out, const void* q,
+                              const void* prompt_k, const void* prompt_v,
+                              void* resp_k, void* resp_v,
+                              const void* lineage, int32_t lineage_capacity,
+                              const void* k_new, const void* v_new,
+                              const float* alibi_slopes,
+                              const int32_t* prompt_lens,
+                              void* workspace, size_t workspace_bytes,
+                              float scale, const segkv_dims* d, void* stream);
+
 /* Bytes of device scratch segkv_sdpa_decode needs for these dimensions (the
  * split-KV partial results of Section 3.3's accumulate step).  0 on invalid
  * dimensions. */

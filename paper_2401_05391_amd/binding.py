@@ -25,7 +25,8 @@ EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_status_string", "segkv_stream_read_probe", "segkv_cache_token_bytes",
            "segkv_cache_standard_bytes", "segkv_cache_segment_bytes", "segkv_response_capacity",
            "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
-           "segkv_rope_append", "segkv_sdpa_decode_ragged", "segkv_sdpa_decode_seq_first_prompt")
+           "segkv_rope_append", "segkv_sdpa_decode_ragged", "segkv_sdpa_decode_seq_first_prompt",
+           "segkv_lineage_bytes", "segkv_lineage_update", "segkv_sdpa_decode_lineage")
 
 
 class SegkvDims(ctypes.Structure):
@@ -65,6 +66,13 @@ def load_library():
                                              ctypes.c_float, dp, vp]
     lib.segkv_sdpa_decode_seq_first_prompt.restype = ctypes.c_int
     lib.segkv_sdpa_decode_seq_first_prompt.argtypes = lib.segkv_sdpa_decode_ragged.argtypes
+    lib.segkv_lineage_bytes.restype = sz
+    lib.segkv_lineage_bytes.argtypes = [dp, i32]
+    lib.segkv_lineage_update.restype = ctypes.c_int
+    lib.segkv_lineage_update.argtypes = [vp, i32, vp, i32, dp, vp]
+    lib.segkv_sdpa_decode_lineage.restype = ctypes.c_int
+    lib.segkv_sdpa_decode_lineage.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz,
+                                              ctypes.c_float, dp, vp]
     lib.segkv_workspace_bytes.restype = sz
     lib.segkv_workspace_bytes.argtypes = [dp]
     lib.segkv_value_stagger_bytes.restype = sz
@@ -179,14 +187,41 @@ def sdpa_decode_seq_first_prompt(out, q, prompt_k, prompt_v, resp_k, resp_v, par
         raise SegkvError(rc, "segkv_sdpa_decode_seq_first_prompt")
 
 
+def lineage_bytes(dims: SegkvDims, capacity: int) -> int:
+    return int(load_library().segkv_lineage_bytes(ctypes.byref(dims), int(capacity)))
+
+
+def lineage_update(lineage, capacity: int, parent_row, t: int, dims: SegkvDims, stream=None) -> None:
+    """One generated token: parent_row is row t of the parent table (None for t == 0)."""
+    rc = load_library().segkv_lineage_update(_ptr(lineage), int(capacity), _ptr(parent_row), int(t),
+                                             ctypes.byref(dims), _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_lineage_update")
+
+
+def sdpa_decode_lineage(out, q, prompt_k, prompt_v, resp_k, resp_v, lineage, capacity: int,
+                        dims: SegkvDims, scale: float, k_new=None, v_new=None, alibi_slopes=None,
+                        prompt_lens=None, workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load_library().segkv_sdpa_decode_lineage(
+        _ptr(out), _ptr(q), _ptr(prompt_k), _ptr(prompt_v), _ptr(resp_k), _ptr(resp_v),
+        _ptr(lineage), int(capacity), _ptr(k_new), _ptr(v_new), _ptr(alibi_slopes),
+        _ptr(prompt_lens), _ptr(workspace), ws_bytes, float(scale), ctypes.byref(dims),
+        _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_sdpa_decode_lineage")
+
+
 def prepare_sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvDims,
                         scale: float, k_new=None, v_new=None, alibi_slopes=None, anc_out=None,
-                        workspace=None, stream=None, prompt_seq_first: bool = False):
+                        workspace=None, stream=None, prompt_seq_first: bool = False,
+                        lineage=None, lineage_capacity: int = 0):
     """Marshal the arguments once; returns a zero-argument callable that enqueues
     the same segkv_sdpa_decode call each time (for launch loops where per-call
     Python marshalling would rival the kernel time).  The tensors must stay alive.
     prompt_seq_first: the prompt tensors are [Lp, B, Hkv, D] and the call is
-    segkv_sdpa_decode_seq_first_prompt."""
+    segkv_sdpa_decode_seq_first_prompt.  lineage: the call is
+    segkv_sdpa_decode_lineage with this list (`parent` is not used)."""
     lib = load_library()
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     vp = ctypes.c_void_p
@@ -194,7 +229,11 @@ def prepare_sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims
                                   v_new, alibi_slopes)]
     tail = ([vp(_ptr(anc_out)), vp(_ptr(workspace)), ctypes.c_size_t(ws_bytes),
              ctypes.c_float(scale), ctypes.byref(dims), vp(_stream_handle(stream))])
-    if prompt_seq_first:
+    if lineage is not None:
+        fn, name = lib.segkv_sdpa_decode_lineage, "segkv_sdpa_decode_lineage"
+        args = (head[:6] + [vp(_ptr(lineage)), ctypes.c_int32(lineage_capacity)] + head[7:]
+                + [vp(None)] + tail[1:])
+    elif prompt_seq_first:
         fn, name, args = (lib.segkv_sdpa_decode_seq_first_prompt,
                           "segkv_sdpa_decode_seq_first_prompt", head + [vp(None)] + tail)
     else:

@@ -177,6 +177,13 @@ Plan make_plan(const segkv_dims* d)
 
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+// A lineage list of `capacity` entries per request can hold `steps` steps of this beam width.
+bool lineage_ok(int32_t capacity, int32_t steps, const segkv_dims* d)
+{
+    return d && d->B >= 1 && d->beam >= 1 && d->beam <= 8 && capacity >= 4 && capacity % 4 == 0 &&
+           steps >= 1 && steps < (1 << 16) && (long)steps * d->beam <= capacity;
+}
+
 }  // namespace
 
 extern "C" {
@@ -242,12 +249,14 @@ int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void*
                      void* resp_k, void* resp_v, const int32_t* parent, const void* k_new,
                      const void* v_new, const float* alibi_slopes, const int32_t* prompt_lens,
                      bool prompt_seq_first, int32_t* anc_out, void* workspace,
-                     size_t workspace_bytes, float scale, const segkv_dims* d, void* stream)
+                     size_t workspace_bytes, float scale, const segkv_dims* d, void* stream,
+                     const void* lineage = nullptr, int32_t lineage_capacity = 0)
 {
     if (!dims_ok(d)) return SEGKV_INVALID_ARG;
+    if (lineage && !lineage_ok(lineage_capacity, d->T, d)) return SEGKV_INVALID_ARG;
     if (!out || !q || !resp_k || !resp_v) return SEGKV_INVALID_ARG;
     if (d->Lp > 0 && (!prompt_k || !prompt_v)) return SEGKV_INVALID_ARG;
-    if (d->beam > 1 && !parent) return SEGKV_INVALID_ARG;
+    if (d->beam > 1 && !parent && !lineage) return SEGKV_INVALID_ARG;
     if ((k_new == nullptr) != (v_new == nullptr)) return SEGKV_INVALID_ARG;
     if (!dims_supported(d)) return SEGKV_UNSUPPORTED;
     if ((long)d->B * d->beam * d->Hq > (1L << 28)) return SEGKV_UNSUPPORTED;
@@ -261,7 +270,9 @@ int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void*
         ((uintptr_t)prompt_lens & 3u))
         return SEGKV_MISALIGNED;
 
+    if (misaligned(lineage)) return SEGKV_MISALIGNED;
     const Plan pl = make_plan(d);
+    if (lineage && !pl.mfma) return SEGKV_UNSUPPORTED;      // the vector-ALU kernel resolves parents only
     const size_t need = pl.ws_ml_bytes + pl.ws_acc_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need)) return SEGKV_WORKSPACE_TOO_SMALL;
 
@@ -277,6 +288,8 @@ int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void*
     p.v_new = (const _Float16*)v_new;
     p.slopes = alibi_slopes;
     p.prompt_lens = prompt_lens;
+    p.lineage = (const uint32_t*)lineage;
+    p.lineage_stride = segkv::kLineageHeaderWords + lineage_capacity;
     if (prompt_seq_first) {
         p.prompt_row_stride = (uint32_t)d->B * d->Hkv * d->D;
         p.prompt_req_stride = (size_t)d->Hkv * d->D;
@@ -326,6 +339,36 @@ int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, con
     return sdpa_decode_impl(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new, v_new,
                             alibi_slopes, prompt_lens, false, anc_out, workspace, workspace_bytes,
                             scale, d, stream);
+}
+
+int segkv_sdpa_decode_lineage(void* out, const void* q, const void* prompt_k, const void* prompt_v,
+                              void* resp_k, void* resp_v, const void* lineage,
+                              int32_t lineage_capacity, const void* k_new, const void* v_new,
+                              const float* alibi_slopes, const int32_t* prompt_lens, void* workspace,
+                              size_t workspace_bytes, float scale, const segkv_dims* d, void* stream)
+{
+    if (!lineage) return SEGKV_INVALID_ARG;
+    return sdpa_decode_impl(out, q, prompt_k, prompt_v, resp_k, resp_v, nullptr, k_new, v_new,
+                            alibi_slopes, prompt_lens, false, nullptr, workspace, workspace_bytes,
+                            scale, d, stream, lineage, lineage_capacity);
+}
+
+size_t segkv_lineage_bytes(const segkv_dims* d, int32_t lineage_capacity)
+{
+    if (!d || d->B < 1 || lineage_capacity < 4 || lineage_capacity % 4 != 0) return 0;
+    return (size_t)d->B * (segkv::kLineageHeaderWords + (size_t)lineage_capacity) * sizeof(uint32_t);
+}
+
+int segkv_lineage_update(void* lineage, int32_t lineage_capacity, const int32_t* parent_row,
+                         int32_t t, const segkv_dims* d, void* stream)
+{
+    if (!lineage || t < 0 || !lineage_ok(lineage_capacity, t + 1, d)) return SEGKV_INVALID_ARG;
+    if (t > 0 && d->beam > 1 && !parent_row) return SEGKV_INVALID_ARG;
+    if (misaligned(lineage) || ((uintptr_t)parent_row & 3u)) return SEGKV_MISALIGNED;
+    const hipError_t e = segkv::launch_lineage_update(
+        (uint32_t*)lineage, parent_row, d->B, d->beam, t,
+        segkv::kLineageHeaderWords + lineage_capacity, (hipStream_t)stream);
+    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
 }
 
 int segkv_sdpa_decode_seq_first_prompt(void* out, const void* q, const void* prompt_k,

@@ -423,6 +423,54 @@ __device__ void build_response_list_wave(WaveListSmem<CAP>& sm, const int32_t* p
     __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
+// Index of the first entry of a lineage list (sorted by step) whose step is >=
+// `step`, found by all 64 lanes of a wave together: every round samples the
+// remaining range at 64 points, so 16 K entries take three dependent loads.
+__device__ __forceinline__ int lineage_lower_bound(const uint32_t* ent, int n, int step, int lane)
+{
+    const uint32_t key = (uint32_t)step << 16;
+    int lo = 0, hi = n;                                   // the answer lies in [lo, hi]
+    while (hi > lo) {
+        const int stride = (hi - lo + 63) / 64;
+        const int idx = lo + lane * stride;
+        const bool ge = (idx < hi) ? (ent[idx] >= key) : true;
+        const unsigned long long votes = __ballot(ge);
+        const int f = votes ? __ffsll((long long)votes) - 1 : 64;   // first sample >= key
+        if (f == 0) return lo;
+        if (stride == 1) return lo + f;
+        hi = min(hi, lo + f * stride);
+        lo = lo + (f - 1) * stride + 1;
+    }
+    return lo;
+}
+
+// The response list of the chunk [s0, s1) taken from the request's lineage list
+// (`hdr`: its header, entries behind it) instead of being derived from the
+// parent table: the entries of those steps are copied to the top of sm.ent with
+// their steps made chunk-local.  Called by all 64 lanes of exactly one wave.
+// Slots and steps are clamped into the chunk so that a list that was not kept up
+// to date cannot send a load outside the request's rows.
+template <int CAP>
+__device__ void load_response_list_wave(WaveListSmem<CAP>& sm, const uint32_t* hdr, int capacity,
+                                        int W, int T, int s0, int s1, int lane)
+{
+    const uint32_t* const ent = hdr + kLineageHeaderWords;
+    const int n = min((int)hdr[0], capacity);
+    const bool whole = (int)hdr[1] == T;                  // the list ends with step T-1
+    const int i0 = (s0 > 0) ? lineage_lower_bound(ent, n, s0, lane) : 0;
+    const int i1 = (s1 < T || !whole) ? lineage_lower_bound(ent, n, s1, lane) : n;
+    const int cnt = min(max(i1 - i0, 0), CAP);
+    const int top = CAP - cnt;
+    for (int i = lane; i < cnt; i += 64) {
+        const uint32_t e = ent[i0 + i];
+        const uint32_t step = (uint32_t)min(max((int)(e >> 16) - s0, 0), s1 - s0 - 1);
+        const uint32_t slot = min((e >> 8) & 0xffu, (uint32_t)(W - 1));
+        sm.ent[top + i] = (step << 16) | (slot << 8) | (e & 0xffu);
+    }
+    __hip_atomic_store(&sm.top, top, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // Any other wave: blocks until ent[want .. CAP) is written or the list is final,
 // whichever comes first (the builder never waits for anything, so this ends).
 // Returns the published top and sets `final`.

@@ -33,6 +33,8 @@ struct SdpaParams {
     int n_rchunks;   // response chunks come first in the chunk index
     uint32_t prompt_row_stride;   // elements between consecutive keys of one request and head
     size_t prompt_req_stride;     // elements between the first keys of consecutive requests
+    const uint32_t* lineage;      // null, or the per-request lineage lists (see segkv_lineage.hip)
+    int lineage_stride;           // 32-bit words per request: header + capacity
     int resp_in_last;   // 1: no response chunks; the last chunk walks its prompt rows and the whole response
 #ifdef SEGKV_TIMING
     unsigned long long* timing;   // tuning builds only: per-wave phase timestamps
@@ -83,6 +85,8 @@ constexpr int mfma_list_capacity(int D, int QT, int NW)
     const int cap = (budget - fixed) / 4;
     return cap < 64 ? 0 : ((cap > 16384 ? 16384 : cap) & ~63);
 }
+// A request's lineage list: {entries, steps covered, 0, 0} ahead of the entries.
+constexpr int kLineageHeaderWords = 4;
 constexpr int kProbeGroups = 4096;       // work-groups (and sink words) of the read probe
 
 hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, int HP, unsigned grid,
@@ -94,6 +98,8 @@ hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_
                              int n_chunks, hipStream_t st);
 hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const void* src_v,
                             size_t bytes, hipStream_t st);
+hipError_t launch_lineage_update(uint32_t* lineage, const int32_t* parent_row, int B, int W, int t,
+                                 int stride, hipStream_t st);
 hipError_t launch_rope_append(const RopeParams& p, int interleaved, int rows, hipStream_t st);
 hipError_t launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
 

@@ -202,7 +202,8 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     const bool has_resp = s1 > s0;                              // uniform over the work-group
     const bool is_builder = has_resp && wave == NW - 1;         // uniform over the wave
     ListRows lrows;
-    if (is_builder && p.W > 1)
+    const bool from_lineage = p.lineage != nullptr && p.W > 1;  // the list is kept across steps
+    if (is_builder && p.W > 1 && !from_lineage)
         load_list_rows(lrows, p.parent, N, p.W, p.T, b, list_last_window_start(s0, s1), lane);
 
     // ---- fused append: the block that owns step T-1 copies the unit's new rows.
@@ -482,7 +483,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     // tiles among themselves; it joins the deal after `skip` rounds (a window of
     // the list costs it about two rounds; measured best among 0 .. 2 per window).
     const int n_win = (s1 - s0 + kListWindow - 1) / kListWindow;
-    const int skip = (has_resp && p.W > 1) ? 2 * n_win - 1 : 0;
+    const int skip = (has_resp && p.W > 1) ? (from_lineage ? 1 : 2 * n_win - 1) : 0;
     const int t_join = skip * (NW - 1);
     int ti = wave < NW - 1 ? wave : t_join + NW - 1;
     if (tid == 0) {
@@ -506,7 +507,12 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     }
     __syncthreads();                                   // Q tile and list flag visible
     SEGKV_STAMP(1);
-    if (is_builder) {
+    if (is_builder && from_lineage) {
+        load_response_list_wave(s_list, p.lineage + (size_t)b * p.lineage_stride,
+                                p.lineage_stride - kLineageHeaderWords, p.W, p.T, s0, s1, lane);
+        need_tile(0);
+        SEGKV_STAMP(2);
+    } else if (is_builder) {
         build_response_list_wave(s_list, p.parent, (g == 0 && qb == 0) ? p.anc_out : nullptr, p.B,
                                  p.W, p.T, b, s0, s1, lrows, lane);
         need_tile(0);                                  // final: this wave has just built it
