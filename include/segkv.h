@@ -210,9 +210,11 @@ int segkv_sdpa_decode_seq_first_prompt(void* out, const void* q,
  *
  * segkv_sdpa_decode_lineage   segkv_sdpa_decode_ragged with the list in place of
  *   the parent table (prompt_lens may be NULL).  The list must have been updated
- *   through step d->T - 1.  Same arithmetic in the same order: the output is
- *   bit-identical to the call with the raw table.  No anc_out.  The workspace is
- *   that of segkv_sdpa_decode.
+ *   through step d->T - 1.  Same tiles and arithmetic as the call with the raw
+ *   table: bit-identical output for T <= 256; beyond that the fp32 partial sums
+ *   of the waves are combined in a different order (the wave that prepares the
+ *   list is free earlier), so outputs agree to rounding.  No anc_out.  The
+ *   workspace is that of segkv_sdpa_decode.
  */
 size_t segkv_lineage_bytes(const segkv_dims* d, int32_t lineage_capacity);
 int segkv_lineage_update(void* lineage, int32_t lineage_capacity, const int32_t* parent_row,

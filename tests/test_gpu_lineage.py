@@ -15,6 +15,18 @@ pytestmark = pytest.mark.gpu
 HDR = 4     # 32-bit words ahead of a request's entries: {entries, steps covered, 0, 0}
 
 
+def _assert_same_attention(from_list, from_table, T, what=""):
+    """Same tiles, same arithmetic.  Up to 256 response steps the tiles are also dealt
+    to the waves in the same order, so the bits are equal; beyond that the wave that
+    prepares the list joins the deal earlier when it only has to copy it, and the
+    fp32 partial sums are combined in a different order."""
+    if T <= 256:
+        assert same_bits(from_list, from_table), what
+    else:
+        diff = np.abs(from_list.astype(np.float64) - from_table.astype(np.float64)).max()
+        assert diff <= 1e-3, (what, diff)
+
+
 def _device_list(buf, b, cap):
     words = buf.cpu().numpy().view(np.uint32).reshape(-1, HDR + cap)[b]
     return int(words[1]), [int(x) for x in words[HDR:HDR + int(words[0])]]
@@ -106,7 +118,7 @@ def test_attention_from_the_list_equals_attention_from_the_parent_table(wl, knob
         torch.cuda.synchronize()
         outs.append((out.cpu().numpy(), rk.cpu().numpy(), rv.cpu().numpy()))
     assert not np.isnan(outs[1][0].astype(np.float32)).any()
-    assert same_bits(outs[1][0], outs[0][0]), "list and parent table must give the same bits"
+    _assert_same_attention(outs[1][0], outs[0][0], wl.T, wl.name)
     assert same_bits(outs[1][1], outs[0][1]) and same_bits(outs[1][2], outs[0][2])
     if with_oracle:
         ork, orv = x["resp_k"].copy(), x["resp_v"].copy()
@@ -114,6 +126,46 @@ def test_attention_from_the_list_equals_attention_from_the_parent_table(wl, knob
         ref, _, _ = oracle.sdpa_decode(x["q"], x["prompt_k"], x["prompt_v"], ork, orv, x["parent"],
                                        wl.W, wl.T, wl.scale, slopes=x["slopes"])
         assert_parity(outs[1][0], ref, wl.name)
+
+
+def _random_beam_workloads(n, seed):
+    """Seeded draw of small beam-search shapes across what the planner looks at."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        D = int(rng.choice([64, 128, 256]))
+        W = int(rng.choice([2, 3, 4, 5, 8]))
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        G = int(rng.choice([1, 1, 2, 4, 8]))
+        out.append(Workload(f"linrnd{seed}_{i}", B=int(rng.integers(1, 5)), W=W, Hq=Hkv * G, Hkv=Hkv, D=D,
+                            Lp=int(rng.choice([0, 1, 33, 100, 257])), T=int(rng.choice([1, 2, 17, 64, 130, 300])),
+                            alibi=bool(rng.integers(0, 2)),
+                            parents=str(rng.choice(["uniform", "uniform", "identity", "zeros"])),
+                            seed=2000 * seed + i))
+    return out
+
+
+@pytest.mark.parametrize("wl", _random_beam_workloads(24, 11), ids=lambda w: w.name)
+def test_random_shapes_list_against_parent_table(wl):
+    import torch
+    import paper_2401_05391_amd as segkv
+    x = make_inputs(wl)
+    dev = torch.device("cuda:0")
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+    cap = ((wl.Tcap * wl.W + 3) // 4) * 4
+    lin = _lineage_for(x["parent"], wl.B, wl.W, wl.T, cap)
+    nbytes = segkv.workspace_bytes(dims)
+    ws = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device=dev) if nbytes else None
+    rk, rv = up(x["resp_k"]), up(x["resp_v"])
+    segkv.append_kv(rk, rv, up(x["k_new"]), up(x["v_new"]), wl.T - 1, dims)
+    a = torch.empty((wl.N, wl.Hq, wl.D), dtype=torch.float16, device=dev)
+    c = torch.full((wl.N, wl.Hq, wl.D), float("nan"), dtype=torch.float16, device=dev)
+    args = (up(x["q"]), up(x["prompt_k"]), up(x["prompt_v"]), rk, rv)
+    segkv.sdpa_decode(a, *args, up(x["parent"]), dims, wl.scale, alibi_slopes=up(x["slopes"]), workspace=ws)
+    segkv.sdpa_decode_lineage(c, *args, lin, cap, dims, wl.scale, alibi_slopes=up(x["slopes"]), workspace=ws)
+    torch.cuda.synchronize()
+    _assert_same_attention(c.cpu().numpy(), a.cpu().numpy(), wl.T, wl.name)
 
 
 def test_step_by_step_generation_with_the_list():
