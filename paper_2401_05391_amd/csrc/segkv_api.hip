@@ -18,6 +18,8 @@ struct Plan {
     int NW;   // waves per work-group of the matrix-core kernel
     int merged, n_chunks, pchunk, rchunk, n_rchunks, n_pchunks, resp_in_last;
     size_t ws_ml_bytes, ws_acc_bytes;
+    int pair;           // 1: two adjacent 64-wide heads per 256-byte row, run as D = 128 (see make_plan)
+    int D, Hq, Hkv;     // the dimensions the kernel is launched with (halved head counts when pair)
     unsigned grid;
 };
 
@@ -61,9 +63,34 @@ bool want_mfma(int /*nq*/, long /*kv_units*/)
 // How the keys of one (request, KV head) unit are cut into work-groups.
 // Enough work-groups to occupy 256 CUs, but chunks long enough that the fp32
 // partials written per chunk stay small next to the K/V bytes the chunk reads.
-Plan make_plan(const segkv_dims* d)
+//
+// Multi-head attention with D = 64 is run as D = 128 with half the heads: Q, K, V
+// and the output of two adjacent heads are one contiguous 256-byte row each, and
+// the kernel's head-pair variant keeps the two heads' products and softmax
+// states apart.  K/V rows then arrive in 256-byte instead of 128-byte pieces
+// (the same bytes laid out as D = 128 stream 10-20% faster).  Pairing halves the
+// number of units, so it is only done when enough remain to fill the device:
+// measured faster from 384 (request, head) units up (+21% at 4096, +8% at 384 to
+// 1024), slower at 256 and below.  SEGKV_PAIR_HEADS=0 / 1 force the choice (A/B
+// measurements, tests).
+Plan make_plan(const segkv_dims* d_in)
 {
     Plan pl{};
+    segkv_dims dd = *d_in;
+    const char* pair_env = std::getenv("SEGKV_PAIR_HEADS");
+    const bool pair_possible = dd.D == 64 && dd.Hq == dd.Hkv && dd.Hkv % 2 == 0 && want_mfma(dd.beam, 0);
+    const bool pair_wanted = pair_env ? pair_env[0] != '0' : (long)dd.B * dd.Hkv >= 384;
+    pl.pair = (pair_possible && pair_wanted) ? 1 : 0;
+    if (pl.pair) {
+        dd.D = 128;
+        dd.Hq /= 2;
+        dd.Hkv /= 2;
+    }
+    const segkv_dims* const d = &dd;
+    const int heads_per_row = pl.pair ? 2 : 1;
+    pl.D = dd.D;
+    pl.Hq = dd.Hq;
+    pl.Hkv = dd.Hkv;
     pl.G = d->Hq / d->Hkv;
     pl.nq = d->beam * pl.G;
     pl.mfma = want_mfma(pl.nq, (long)d->B * d->Hkv) ? 1 : 0;
@@ -106,9 +133,10 @@ Plan make_plan(const segkv_dims* d)
         const int nw_env = env_int("SEGKV_MFMA_WAVES", 0);
         if (pl.QB == 16 && d->D <= 128 &&
             (nw_env == 4 || (nw_env == 0 && kv_units > 256 &&
-                             d->T * d->beam <= segkv::mfma_list_capacity(d->D, pl.QB, 4))))
+                             d->T * d->beam <=
+                                 segkv::mfma_list_capacity(d->D, pl.QB, 4, heads_per_row))))
             pl.NW = 4;
-        max_steps_merged = segkv::mfma_list_capacity(d->D, pl.QB, pl.NW) / d->beam;
+        max_steps_merged = segkv::mfma_list_capacity(d->D, pl.QB, pl.NW, heads_per_row) / d->beam;
         if (max_steps_merged > 65535) max_steps_merged = 65535;
         max_steps = max_steps_merged < segkv::kMaxStepsPerChunk ? max_steps_merged
                                                                 : segkv::kMaxStepsPerChunk;
@@ -168,7 +196,8 @@ Plan make_plan(const segkv_dims* d)
     }
     const size_t NQ = (size_t)d->B * d->beam * d->Hq;
     if (pl.n_chunks > 1) {
-        pl.ws_ml_bytes = ((size_t)pl.n_chunks * NQ * 2 * sizeof(float) + 15) & ~(size_t)15;
+        pl.ws_ml_bytes =
+            ((size_t)pl.n_chunks * NQ * heads_per_row * 2 * sizeof(float) + 15) & ~(size_t)15;
         pl.ws_acc_bytes = (size_t)pl.n_chunks * NQ * d->D * sizeof(float);
     }
     pl.grid = (unsigned)(units * pl.n_chunks);
@@ -212,7 +241,8 @@ size_t segkv_value_stagger_bytes(const segkv_dims* d)
 {
     if (!dims_ok(d) || !dims_supported(d)) return 0;
     // only the per-head column streams of the matrix-core kernel gain from it
-    return (make_plan(d).mfma && d->D * 2 == 256) ? 256 : 0;
+    const Plan pl = make_plan(d);
+    return (pl.mfma && pl.D * 2 == 256) ? 256 : 0;
 }
 
 int segkv_append_kv(void* resp_k, void* resp_v, const void* k_new, const void* v_new, int32_t t,
@@ -301,7 +331,8 @@ int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void*
     p.ws_ml = need ? (float*)workspace : nullptr;
     p.ws_acc = need ? (float*)((char*)workspace + pl.ws_ml_bytes) : nullptr;
     p.scale2 = scale * 1.4426950408889634f;
-    p.B = d->B; p.W = d->beam; p.Hq = d->Hq; p.Hkv = d->Hkv; p.G = pl.G; p.Lp = d->Lp; p.T = d->T;
+    p.B = d->B; p.W = d->beam; p.Hq = pl.Hq; p.Hkv = pl.Hkv; p.G = pl.G; p.Lp = d->Lp; p.T = d->T;
+    p.head_pairs = pl.pair;
     p.nq = pl.nq;
     p.n_qblocks = pl.n_qblocks;
     p.merged = pl.merged;
@@ -317,7 +348,7 @@ int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void*
 #endif
 
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, d->D, pl.QB, pl.NW, pl.grid, st)
+    hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, pl.D, pl.QB, pl.NW, pl.grid, st)
                            : segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.HP, pl.grid, st);
     if (e != hipSuccess) return SEGKV_HIP_ERROR;
     if (pl.n_chunks > 1) {

@@ -35,6 +35,7 @@ struct SdpaParams {
     size_t prompt_req_stride;     // elements between the first keys of consecutive requests
     const uint32_t* lineage;      // null, or the per-request lineage lists (see segkv_lineage.hip)
     int lineage_stride;           // 32-bit words per request: header + capacity
+    int head_pairs;     // 1: every row holds two adjacent heads of D/2 elements (D = 128 kernel, 64-wide heads)
     int resp_in_last;   // 1: no response chunks; the last chunk walks its prompt rows and the whole response
 #ifdef SEGKV_TIMING
     unsigned long long* timing;   // tuning builds only: per-wave phase timestamps
@@ -78,9 +79,10 @@ constexpr int mfma_region_bytes(int D, int QT)
     const int merge = QT * (D + 4) * 4;
     return tiles > merge ? tiles : merge;
 }
-constexpr int mfma_list_capacity(int D, int QT, int NW)
+constexpr int mfma_list_capacity(int D, int QT, int NW, int heads_per_row = 1)
 {
-    const int fixed = NW * mfma_region_bytes(D, QT) + QT * (2 * D + 16) + NW * QT * 8 + 64;
+    const int fixed = NW * mfma_region_bytes(D, QT) + QT * (2 * D + 16) +
+                      NW * heads_per_row * QT * 8 + 64;
     const int budget = (NW == 8 ? 160 : 80) * 1024 - 256;
     const int cap = (budget - fixed) / 4;
     return cap < 64 ? 0 : ((cap > 16384 ? 16384 : cap) & ~63);

@@ -87,7 +87,13 @@ struct DecodeGeometry {
     static_assert(QT == 16 || KT == 32, "the 32-slot shape multiplies 32-key tiles");
 };
 
-template <int D, int NW, int QT, bool SHARED>
+// PAIR: every 2D-byte row holds TWO adjacent KV heads of D/2 elements each (a
+// D/2 = 64 multi-head model seen as rows of 128): one work-group serves both
+// heads, so that K/V rows are fetched in 256-byte instead of 128-byte pieces
+// (measured +10-20% of HBM bandwidth).  Q, K, V and the output have the same
+// memory layout either way; the products are block-diagonal (each head contracts
+// over its own half of the row) and every head keeps its own softmax state.
+template <int D, int NW, int QT, bool SHARED, bool PAIR = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void sdpa_decode_mfma_kernel(SdpaParams p)
 {
@@ -100,14 +106,17 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     // accumulator registers per lane: O^T is D x QT fp32 over 64 lanes
     constexpr int NOB = WIDE ? D / 32 : D / 16;        // blocks of the PV product
     constexpr int OBR = WIDE ? 16 : 4;                 // registers per block
-    constexpr int NSR = WIDE ? 16 : (KT / 16) * 4;     // S^T registers per lane and tile
+    constexpr int NSR = WIDE ? 16 : (KT / 16) * 4;     // S^T registers per lane, tile and head
+    constexpr int NH = PAIR ? 2 : 1;                   // heads per row
+    constexpr int DH = D / NH;                         // elements per head
+    static_assert(!PAIR || (!WIDE && D == 128), "head pairs: 16-slot shape, 64-element heads");
 
     __shared__ __align__(16) unsigned char s_region[NW * REGIONB];
     __shared__ __align__(16) unsigned char s_q[QT * ROWB];   // Q^T operand, shared by the waves
-    constexpr int LISTCAP = mfma_list_capacity(D, QT, NW);
+    constexpr int LISTCAP = mfma_list_capacity(D, QT, NW, PAIR ? 2 : 1);
     static_assert(LISTCAP >= 64, "no room for a response list");
     __shared__ WaveListSmem<LISTCAP> s_list;
-    __shared__ float s_ml[NW][QT][2];
+    __shared__ float s_ml[NW][NH][QT][2];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -177,7 +186,9 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     const int lqc = q_valid ? lq : (p.nq - 1);
     const int qbeam = lqc / p.G;
     const int hq = g * p.G + (lqc % p.G);
-    const float slope2 = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
+    float slope2[NH];
+#pragma unroll
+    for (int hd = 0; hd < NH; ++hd) slope2[hd] = p.slopes ? p.slopes[NH * hq + hd] * kLog2e : 0.0f;
     const int qpos = Lp + p.T - 1;
     // Requests that later steps depend on go out first, in this order: the Q
     // chunks this thread stages, its row of the parent table, then (below) the
@@ -227,8 +238,12 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     const uint32_t* const ent = s_list.ent;
     SEGKV_PHASE_DECL;
     // ---- running state: reference max and partial sum per lane, O^T accumulators ----
-    float m_ref = kEmptyMax;
-    float l_part = 0.0f;            // sum of p over this lane's keys of every tile
+    float m_ref[NH], l_part[NH];    // l_part: sum of p over this lane's keys of every tile
+#pragma unroll
+    for (int hd = 0; hd < NH; ++hd) {
+        m_ref[hd] = kEmptyMax;
+        l_part[hd] = 0.0f;
+    }
     typedef float acc_t __attribute__((ext_vector_type(OBR)));
     acc_t o_acc[NOB];
 #pragma unroll
@@ -260,7 +275,7 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     auto key_row = [&](int r) { return (WIDE ? 8 : 16) * (r >> 2) + 4 * h + (r & 3); };
     auto compute_tile = [&](int mode, int base, int lo) __attribute__((always_inline)) {
         // S^T = K . Q^T
-        float s[NSR];
+        float s[NH][NSR];
         if constexpr (WIDE) {
             float16_t acc;
 #pragma unroll
@@ -273,75 +288,82 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq, acc, 0, 0, 0);
             }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = acc[r];
+            for (int r = 0; r < 16; ++r) s[0][r] = acc[r];
         } else {
-            // 16 keys x 16 queries per MFMA, 32 head-dim elements per step
+            // 16 keys x 16 queries per MFMA, 32 head-dim elements per step; a head
+            // contracts over its own DH / 32 steps of the row
 #pragma unroll
             for (int kb = 0; kb < KT / 16; ++kb) {
-                float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                for (int t = 0; t < D / 32; ++t) {
-                    const int col = (4 * t + h) << 4;
-                    const half8_t a =
-                        *reinterpret_cast<const half8_t*>(k_tile + (16 * kb + n) * ROWB + col);
-                    const half8_t bq = *reinterpret_cast<const half8_t*>(s_q + n * ROWB + col);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq, acc, 0, 0, 0);
+                for (int hd = 0; hd < NH; ++hd) {
+                    float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                    for (int t = hd * (DH / 32); t < (hd + 1) * (DH / 32); ++t) {
+                        const int col = (4 * t + h) << 4;
+                        const half8_t a =
+                            *reinterpret_cast<const half8_t*>(k_tile + (16 * kb + n) * ROWB + col);
+                        const half8_t bq = *reinterpret_cast<const half8_t*>(s_q + n * ROWB + col);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq, acc, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) s[hd][4 * kb + r] = acc[r];
                 }
-#pragma unroll
-                for (int r = 0; r < 4; ++r) s[4 * kb + r] = acc[r];
             }
         }
         SEGKV_PHASE(1);
-        // logits, tile maximum for this lane's query
-        float m_tile = -INFINITY;
-        if (mode == 0) {
+        // logits, tile maximum for this lane's query; P = 2^(z - m_ref), fp16 for the
+        // PV product -- per head of the row
+        _Float16 ph[NH][NSR];
+#pragma unroll
+        for (int hd = 0; hd < NH; ++hd) {
+            float m_tile = -INFINITY;
+            if (mode == 0) {
+#pragma unroll
+                for (int r = 0; r < NSR; ++r) {
+                    s[hd][r] *= p.scale2;
+                    m_tile = fmaxf(m_tile, s[hd][r]);
+                }
+            } else if (mode == 1) {
+#pragma unroll
+                for (int r = 0; r < NSR; ++r) {
+                    const int kpos = base + key_row(r);
+                    const float z = s[hd][r] * p.scale2 + slope2[hd] * (float)(kpos - qpos);
+                    s[hd][r] = kpos < k1 ? z : -INFINITY;
+                    m_tile = fmaxf(m_tile, s[hd][r]);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < NSR; ++r) {
+                    const int e = base + key_row(r);
+                    const uint32_t en = ent[max(e, lo)];
+                    const int kpos = Lp + s0 + (int)(en >> 16);
+                    const float z = s[hd][r] * p.scale2 + slope2[hd] * (float)(kpos - qpos);
+                    const bool vis = (e >= lo) && ((en >> qbeam) & 1u);
+                    s[hd][r] = vis ? z : -INFINITY;
+                    m_tile = fmaxf(m_tile, s[hd][r]);
+                }
+            }
+            // Move the reference maximum only when a tile exceeds it by the slack.  The
+            // lanes that share a query hold different keys, but the vote is wave-wide, so
+            // their maxima need to be exchanged only when the reference does move.
+            if (__any(m_tile > m_ref[hd] + kRescaleSlack)) {
+                if constexpr (!WIDE) m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16));
+                m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+                const float m_new = fmaxf(m_ref[hd], m_tile);
+                const float corr = fast_exp2(m_ref[hd] - m_new);
+                m_ref[hd] = m_new;
+                l_part[hd] *= corr;
+#pragma unroll
+                for (int ob = hd * (NOB / NH); ob < (hd + 1) * (NOB / NH); ++ob)
+#pragma unroll
+                    for (int r = 0; r < OBR; ++r) o_acc[ob][r] *= corr;
+            }
 #pragma unroll
             for (int r = 0; r < NSR; ++r) {
-                s[r] *= p.scale2;
-                m_tile = fmaxf(m_tile, s[r]);
+                const float pr = fast_exp2(s[hd][r] - m_ref[hd]);
+                l_part[hd] += pr;
+                ph[hd][r] = (_Float16)pr;
             }
-        } else if (mode == 1) {
-#pragma unroll
-            for (int r = 0; r < NSR; ++r) {
-                const int kpos = base + key_row(r);
-                const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
-                s[r] = kpos < k1 ? z : -INFINITY;
-                m_tile = fmaxf(m_tile, s[r]);
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < NSR; ++r) {
-                const int e = base + key_row(r);
-                const uint32_t en = ent[max(e, lo)];
-                const int kpos = Lp + s0 + (int)(en >> 16);
-                const float z = s[r] * p.scale2 + slope2 * (float)(kpos - qpos);
-                const bool vis = (e >= lo) && ((en >> qbeam) & 1u);
-                s[r] = vis ? z : -INFINITY;
-                m_tile = fmaxf(m_tile, s[r]);
-            }
-        }
-        // Move the reference maximum only when a tile exceeds it by the slack.  The
-        // lanes that share a query hold different keys, but the vote is wave-wide, so
-        // their maxima need to be exchanged only when the reference does move.
-        if (__any(m_tile > m_ref + kRescaleSlack)) {
-            if constexpr (!WIDE) m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16));
-            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
-            const float m_new = fmaxf(m_ref, m_tile);
-            const float corr = fast_exp2(m_ref - m_new);
-            m_ref = m_new;
-            l_part *= corr;
-#pragma unroll
-            for (int ob = 0; ob < NOB; ++ob)
-#pragma unroll
-                for (int r = 0; r < OBR; ++r) o_acc[ob][r] *= corr;
-        }
-        // P = 2^(z - m_ref), fp16 for the PV product
-        _Float16 ph[NSR];
-#pragma unroll
-        for (int r = 0; r < NSR; ++r) {
-            const float pr = fast_exp2(s[r] - m_ref);
-            l_part += pr;
-            ph[r] = (_Float16)pr;
         }
         SEGKV_PHASE(2);
         // O^T += V^T . P^T.  The A operand wants, per lane, several keys of one
@@ -363,8 +385,9 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
                     const half4_t lo = lds_read_tr16(v_tile + off);
                     const half4_t hi = lds_read_tr16(v_tile + off + 8 * VROWB);
                     const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                    const half8_t pb = {ph[8 * u + 0], ph[8 * u + 1], ph[8 * u + 2], ph[8 * u + 3],
-                                        ph[8 * u + 4], ph[8 * u + 5], ph[8 * u + 6], ph[8 * u + 7]};
+                    const half8_t pb = {ph[0][8 * u + 0], ph[0][8 * u + 1], ph[0][8 * u + 2],
+                                        ph[0][8 * u + 3], ph[0][8 * u + 4], ph[0][8 * u + 5],
+                                        ph[0][8 * u + 6], ph[0][8 * u + 7]};
                     o_acc[ob] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb, o_acc[ob], 0, 0, 0);
                 }
                 // keep the operand reads of later blocks from piling up in registers
@@ -377,9 +400,12 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             const int tr_base = (4 * h + (li >> 2)) * VROWB + ((4 * (li & 3)) << 1);
 #pragma unroll
             for (int kb = 0; kb < KT / 16; ++kb) {
-                const half4_t pb = {ph[4 * kb + 0], ph[4 * kb + 1], ph[4 * kb + 2], ph[4 * kb + 3]};
 #pragma unroll
                 for (int ob = 0; ob < NOB; ++ob) {
+                    constexpr int kBlocksPerHead = NOB / NH;       // output blocks of one head
+                    const int hd = ob / kBlocksPerHead;
+                    const half4_t pb = {ph[hd][4 * kb + 0], ph[hd][4 * kb + 1], ph[hd][4 * kb + 2],
+                                        ph[hd][4 * kb + 3]};
                     const half4_t a = lds_read_tr16(v_tile + tr_base + (16 * kb) * VROWB + ob * 32);
                     o_acc[ob] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, pb, o_acc[ob], 0, 0, 0);
                 }
@@ -540,8 +566,11 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
 
     SEGKV_STAMP(4);
     // ---- merge the waves through LDS (each wave reuses its own tile region) ----
-    l_part += __shfl_xor(l_part, 32);
-    if constexpr (!WIDE) l_part += __shfl_xor(l_part, 16);
+#pragma unroll
+    for (int hd = 0; hd < NH; ++hd) {
+        l_part[hd] += __shfl_xor(l_part[hd], 32);
+        if constexpr (!WIDE) l_part[hd] += __shfl_xor(l_part[hd], 16);
+    }
     float* const mrg = reinterpret_cast<float*>(region);
     // register j of block ob is O^T[d][n] with d = (WIDE ? 32 ob + 8 (j/4) + 4 h : 16 ob + 4 h) + j%4
 #pragma unroll
@@ -554,8 +583,11 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             *reinterpret_cast<float4_t*>(mrg + n * MROW + d0) = v4;
         }
     if (h == 0) {
-        s_ml[wave][n][0] = m_ref;
-        s_ml[wave][n][1] = l_part;
+#pragma unroll
+        for (int hd = 0; hd < NH; ++hd) {
+            s_ml[wave][hd][n][0] = m_ref[hd];
+            s_ml[wave][hd][n][1] = l_part[hd];
+        }
     }
     __syncthreads();
     SEGKV_STAMP(5);
@@ -565,15 +597,16 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     for (int idx = tid; idx < nq_here * (D / 4); idx += NT) {
         const int qn = idx / (D / 4);
         const int d4 = (idx % (D / 4)) * 4;
-        float mm = s_ml[0][qn][0];
+        const int hd = d4 / DH;                         // which head of the row these columns belong to
+        float mm = s_ml[0][hd][qn][0];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) mm = fmaxf(mm, s_ml[w][qn][0]);
+        for (int w = 1; w < NW; ++w) mm = fmaxf(mm, s_ml[w][hd][qn][0]);
         float ll = 0.0f;
         float4_t aa = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
-            const float f = fast_exp2(s_ml[w][qn][0] - mm);
-            ll += s_ml[w][qn][1] * f;
+            const float f = fast_exp2(s_ml[w][hd][qn][0] - mm);
+            ll += s_ml[w][hd][qn][1] * f;
             const float4_t a = *reinterpret_cast<const float4_t*>(
                 reinterpret_cast<const float*>(s_region + w * REGIONB) + qn * MROW + d4);
             aa += a * f;
@@ -592,9 +625,9 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             *reinterpret_cast<half4_t*>(p.out + row * D + d4) = o;
         } else {
             *reinterpret_cast<float4_t*>(p.ws_acc + ((size_t)chunk * NQ + row) * D + d4) = aa;
-            if (d4 == 0) {
-                p.ws_ml[((size_t)chunk * NQ + row) * 2 + 0] = mm;
-                p.ws_ml[((size_t)chunk * NQ + row) * 2 + 1] = ll;
+            if (d4 % DH == 0) {                         // one (m, l) pair per query and head
+                p.ws_ml[(((size_t)chunk * NQ + row) * NH + hd) * 2 + 0] = mm;
+                p.ws_ml[(((size_t)chunk * NQ + row) * NH + hd) * 2 + 1] = ll;
             }
         }
     }
@@ -607,6 +640,13 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
 template <int D, int NW, int QT>
 static void launch_variant(const SdpaParams& p, unsigned grid, hipStream_t st)
 {
+    if constexpr (D == 128 && QT == 16) {
+        if (p.head_pairs) {     // planner: never with several query blocks
+            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT, false, true>), dim3(grid),
+                               dim3(NW * 64), 0, st, p);
+            return;
+        }
+    }
     // several query blocks per unit: the variant whose blocks share K/V rows through L2
     if (p.n_qblocks > 1)
         hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT, true>), dim3(grid), dim3(NW * 64), 0,

@@ -87,6 +87,9 @@ CASES = [
     # looking up its own range of the list
     (Workload("lin_response_chunks", B=1, W=4, Hq=4, Hkv=4, D=128, Lp=96, T=1300, seed=606), {}, False),
     (Workload("lin_greedy", B=4, W=1, Hq=8, Hkv=8, D=128, Lp=50, T=20, parents="identity", seed=607), {}, True),
+    # two adjacent 64-wide heads per work-group
+    (Workload("lin_head_pairs", B=2, W=4, Hq=4, Hkv=4, D=64, Lp=70, T=90, alibi=True, seed=608),
+     dict(SEGKV_PAIR_HEADS=1), True),
 ]
 
 

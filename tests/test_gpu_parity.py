@@ -379,6 +379,84 @@ def test_sequence_first_prompt_layout(wl, lens, path, knobs, ragged, planner_env
     assert same_bits(got, outs[0][0]), "the two prompt layouts must give the same bits"
 
 
+# Multi-head shapes with D = 64 that the library may run as pairs of adjacent
+# heads (one 256-byte row per pair, block-diagonal products, one softmax state
+# per head): forced on here, whatever the number of units, and once left to the
+# planner's own threshold.
+PAIRED = [
+    (Workload("pair_tiny", B=1, W=4, Hq=4, Hkv=4, D=64, Lp=32, T=8, seed=501), {}),
+    (Workload("pair_alibi", B=2, W=4, Hq=6, Hkv=6, D=64, Lp=150, T=40, alibi=True, seed=502), {}),
+    (Workload("pair_greedy", B=5, W=1, Hq=8, Hkv=8, D=64, Lp=300, T=17, parents="identity", alibi=True, seed=503), {}),
+    (Workload("pair_w8", B=1, W=8, Hq=2, Hkv=2, D=64, Lp=65, T=130, seed=504), {}),
+    (Workload("pair_split_kv", B=1, W=3, Hq=4, Hkv=4, D=64, Lp=700, T=300, alibi=True, seed=505), {}),
+    (Workload("pair_single_launch", B=3, W=4, Hq=4, Hkv=4, D=64, Lp=120, T=40, seed=506), dict(SEGKV_TARGET_GROUPS=1)),
+    (Workload("pair_four_waves", B=3, W=2, Hq=4, Hkv=4, D=64, Lp=90, T=33, seed=507),
+     dict(SEGKV_TARGET_GROUPS=1, SEGKV_MFMA_WAVES=4)),
+    (Workload("pair_response_chunks", B=1, W=4, Hq=2, Hkv=2, D=64, Lp=40, T=1300, seed=508), {}),
+]
+
+
+@pytest.mark.parametrize("wl,knobs", PAIRED, ids=[c[0].name for c in PAIRED])
+def test_head_pairs_forced(wl, knobs, planner_env, monkeypatch):
+    monkeypatch.setenv("SEGKV_PAIR_HEADS", "1")
+    planner_env(**knobs)
+    x = make_inputs(wl)
+    ref = oracle_reference(wl, x)
+    res = run_gpu(wl, x, fused=True)
+    _check(wl, x, res, *ref, what=wl.name)
+
+
+@pytest.mark.parametrize("pair", ["0", "auto"])
+def test_head_pairs_at_the_planners_threshold(pair, monkeypatch):
+    # 384 (request, head) units: paired by default, one head per work-group when switched off
+    if pair != "auto":
+        monkeypatch.setenv("SEGKV_PAIR_HEADS", pair)
+    wl = Workload("pair_auto", B=24, W=2, Hq=16, Hkv=16, D=64, Lp=40, T=6, alibi=True, seed=509)
+    x = make_inputs(wl)
+    ref = oracle_reference(wl, x)
+    res = run_gpu(wl, x, fused=True)
+    _check(wl, x, res, *ref, what=f"{wl.name}/{pair}")
+
+
+def test_head_pairs_with_per_request_prompt_lengths_in_both_prompt_layouts(monkeypatch):
+    import torch
+    import paper_2401_05391_amd as segkv
+    from oracle import segkv_oracle as oracle
+    monkeypatch.setenv("SEGKV_PAIR_HEADS", "1")
+    wl = Workload("pair_ragged", B=3, W=4, Hq=4, Hkv=4, D=64, Lp=120, T=40, alibi=True, seed=510)
+    lens = np.asarray([120, 5, 77], dtype=np.int32)
+    x = make_inputs(wl)
+    for b, lb in enumerate(lens):
+        x["prompt_k"][b, lb:] = np.float16(np.nan)
+        x["prompt_v"][b, lb:] = np.float16(np.nan)
+    dev = torch.device("cuda:0")
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+    nbytes = segkv.workspace_bytes(dims)
+    ork, orv = x["resp_k"].copy(), x["resp_v"].copy()
+    oracle.append_kv(ork, orv, x["k_new"], x["v_new"], wl.T - 1)
+    ref, ref_anc = oracle.sdpa_decode_ragged(x["q"], x["prompt_k"], x["prompt_v"], ork, orv, x["parent"],
+                                             wl.W, wl.T, wl.scale, lens, slopes=x["slopes"])
+    for seq_first in (False, True):
+        pk, pv = up(x["prompt_k"]), up(x["prompt_v"])
+        if seq_first:
+            pk, pv = pk.transpose(0, 1).contiguous(), pv.transpose(0, 1).contiguous()
+        rk, rv = up(x["resp_k"]), up(x["resp_v"])
+        ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=dev) if nbytes else None
+        out = torch.full((wl.N, wl.Hq, wl.D), float("nan"), dtype=torch.float16, device=dev)
+        anc = torch.full((wl.T, wl.N), -1, dtype=torch.int32, device=dev)
+        kw = dict(k_new=up(x["k_new"]), v_new=up(x["v_new"]), alibi_slopes=up(x["slopes"]), anc_out=anc, workspace=ws)
+        if seq_first:
+            segkv.sdpa_decode_seq_first_prompt(out, up(x["q"]), pk, pv, rk, rv, up(x["parent"]), dims, wl.scale,
+                                               prompt_lens=up(lens), **kw)
+        else:
+            segkv.sdpa_decode_ragged(out, up(x["q"]), pk, pv, rk, rv, up(x["parent"]), up(lens), dims, wl.scale, **kw)
+        torch.cuda.synchronize()
+        assert np.array_equal(anc.cpu().numpy(), ref_anc)
+        assert_parity(out.cpu().numpy(), ref, f"{wl.name}/seq_first={seq_first}")
+        assert same_bits(rk.cpu().numpy(), ork) and same_bits(rv.cpu().numpy(), orv)
+
+
 def _random_workloads(n, seed):
     """Seeded draw of small shapes across every dimension the planner looks at."""
     rng = np.random.default_rng(seed)
