@@ -106,3 +106,41 @@ def test_value_stagger_hint_is_host_only_and_bounded():
         assert 0 <= v < 1024 and v % 16 == 0
     assert segkv.value_stagger_bytes(segkv.make_dims(B=0, beam=4, Hq=4, Hkv=4, D=64, Lp=32, T=8,
                                                      Tcap=16)) == 0
+
+
+def test_lineage_entry_points_reject_bad_arguments_without_a_device():
+    lib = segkv.load_library()
+    d = segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=64, T=5, Tcap=16)
+    ref = ctypes.byref(d)
+    # size of the list buffer: per request a 4-word header and `capacity` entries of 4 bytes
+    assert lib.segkv_lineage_bytes(ref, 64) == 2 * (4 + 64) * 4
+    assert lib.segkv_lineage_bytes(ref, 62) == 0            # not a multiple of 4
+    assert lib.segkv_lineage_bytes(None, 64) == 0
+    upd = lib.segkv_lineage_update
+    assert upd(None, 64, FAKE, 1, ref, None) == binding.SEGKV_INVALID_ARG        # no list
+    assert upd(FAKE, 62, FAKE, 1, ref, None) == binding.SEGKV_INVALID_ARG        # capacity % 4
+    assert upd(FAKE, 64, FAKE, 16, ref, None) == binding.SEGKV_INVALID_ARG       # 17 steps x 4 beams > 64
+    assert upd(FAKE, 64, FAKE, -1, ref, None) == binding.SEGKV_INVALID_ARG
+    assert upd(FAKE, 64, None, 3, ref, None) == binding.SEGKV_INVALID_ARG        # parent row needed after step 0
+    assert upd(FAKE + 4, 64, FAKE, 3, ref, None) == binding.SEGKV_MISALIGNED
+    dec = lib.segkv_sdpa_decode_lineage
+    args = lambda lin, cap: (FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, lin, cap, None, None, None, None, FAKE, 0,
+                             0.125, ref, None)
+    assert dec(*args(None, 64)) == binding.SEGKV_INVALID_ARG
+    assert dec(*args(FAKE, 16)) == binding.SEGKV_INVALID_ARG                     # 5 steps x 4 beams > 16
+    assert dec(*args(FAKE + 8, 64)) == binding.SEGKV_MISALIGNED
+
+
+def test_sequence_first_prompt_entry_point_validates_like_the_batch_first_one():
+    lib = segkv.load_library()
+    d = segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=64, T=5, Tcap=16)
+    call = lambda d_, out=FAKE, pk=FAKE: lib.segkv_sdpa_decode_seq_first_prompt(
+        out, FAKE, pk, FAKE, FAKE, FAKE, FAKE, None, None, None, None, None, FAKE, 0, 0.125,
+        ctypes.byref(d_), None)
+    assert call(d, out=None) == binding.SEGKV_INVALID_ARG
+    assert call(d, pk=None) == binding.SEGKV_INVALID_ARG
+    assert call(d, pk=FAKE + 2) == binding.SEGKV_MISALIGNED
+    bad = segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=96, Lp=64, T=5, Tcap=16)
+    assert call(bad) == binding.SEGKV_UNSUPPORTED
+    wide = segkv.make_dims(B=1 << 20, beam=1, Hq=64, Hkv=64, D=128, Lp=1, T=1, Tcap=1)
+    assert call(wide) == binding.SEGKV_UNSUPPORTED           # B*Hkv*D beyond the 32-bit tile offsets
