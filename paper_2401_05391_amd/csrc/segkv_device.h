@@ -207,15 +207,16 @@ __device__ void build_response_list(ResponseListSmem& sm, const int32_t* parent,
 
 // ---------------------------------------------------------------------------
 // The same list built by ONE wave, with no work-group barrier: the other waves
-// of the group keep streaming prompt tiles meanwhile and pick the list up
-// through `ready` when they reach their first response tile.
+// of the group keep streaming prompt tiles meanwhile and take what is finished of
+// the list (`top`, then `ready`) when they reach a response tile.
 //
 // Beam maps are kept one BYTE per beam here (byte j = slot of beam j), so that a
 // composition is two v_perm_b32 byte permutes.  The chunk's steps are walked in
 // windows of 256 (4 per lane) from the last window to the first -- the slot map
 // of a step is a suffix composition, so it flows backwards -- and each window's
-// entries are placed below the previous window's: the finished list occupies
-// ent[base .. base + total), ordered by step, whatever the number of windows.
+// entries are placed below the previous window's, from the end of the buffer
+// down: after every window ent[top .. CAP) is a finished part of the list, ordered
+// by step, and the whole list once the first window is done.
 // ---------------------------------------------------------------------------
 constexpr int kListStepsPerLane = 4;
 constexpr int kListWindow = 64 * kListStepsPerLane;
