@@ -131,6 +131,40 @@ def test_attention_from_the_list_equals_attention_from_the_parent_table(wl, knob
         assert_parity(outs[1][0], ref, wl.name)
 
 
+@pytest.mark.parametrize("name", ["llama2_70b_gqa", "bloom176b_alibi"])
+def test_full_size_list_against_parent_table(name):
+    # benchmark configurations at full size, fused append: the same bits either way
+    import torch
+    import paper_2401_05391_amd as segkv
+    from paper_2401_05391_amd.workloads import CONFIGS
+    wl = CONFIGS[name]
+    x = make_inputs(wl)
+    dev = torch.device("cuda:0")
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+    cap = wl.Tcap * wl.W
+    lin = _lineage_for(x["parent"], wl.B, wl.W, wl.T, cap)
+    nbytes = segkv.workspace_bytes(dims)
+    ws = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device=dev) if nbytes else None
+    q, pk, pv = up(x["q"]), up(x["prompt_k"]), up(x["prompt_v"])
+    kn, vn, slopes = up(x["k_new"]), up(x["v_new"]), up(x["slopes"])
+    outs = []
+    for use_list in (False, True):
+        rk, rv = up(x["resp_k"]), up(x["resp_v"])
+        out = torch.full((wl.N, wl.Hq, wl.D), float("nan"), dtype=torch.float16, device=dev)
+        if use_list:
+            segkv.sdpa_decode_lineage(out, q, pk, pv, rk, rv, lin, cap, dims, wl.scale, k_new=kn, v_new=vn,
+                                      alibi_slopes=slopes, workspace=ws)
+        else:
+            segkv.sdpa_decode(out, q, pk, pv, rk, rv, up(x["parent"]), dims, wl.scale, k_new=kn, v_new=vn,
+                              alibi_slopes=slopes, workspace=ws)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+        assert same_bits(rk[wl.T - 1].cpu().numpy(), x["k_new"])
+        del rk, rv
+    assert same_bits(outs[1], outs[0])
+
+
 def _random_beam_workloads(n, seed):
     """Seeded draw of small beam-search shapes across what the planner looks at."""
     rng = np.random.default_rng(seed)

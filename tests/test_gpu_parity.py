@@ -272,6 +272,18 @@ def test_full_size_configs(name):
     assert same_bits(res["resp_v"][wl.T - 1], x["v_new"])
 
 
+def test_full_size_d64_multi_head_shape_runs_as_head_pairs():
+    # 1024 (request, head) units of 64-element heads: the planner pairs adjacent heads
+    import paper_2401_05391_amd as segkv
+    wl = Workload("mha_d64_beam4", B=32, W=4, Hq=32, Hkv=32, D=64, Lp=1024, T=128, alibi=True, seed=12)
+    dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+    assert segkv.value_stagger_bytes(dims) == 256          # rows of 256 bytes: the paired plan is in use
+    x = make_inputs(wl)
+    res = run_gpu(wl, x, fused=True)
+    ref_out, ref_anc, ref_rk, ref_rv = oracle_reference(wl, x)
+    _check(wl, x, res, ref_out, ref_anc, ref_rk, ref_rv, wl.name)
+
+
 @pytest.mark.parametrize("bs", [1, 4])
 def test_fig6_llama2_13b_shape(bs):
     # the paper's own kernel experiment (Section 4.1, Figure 6) at two of its batch
