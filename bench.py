@@ -248,12 +248,43 @@ def cpu_baseline(wl, x, bytes_unique, budget_s, U):
         times.append(run(nreq))
     t = float(np.median(times))
     frac = nreq / wl.B
+    tiny_us = tiny_single_thread_us(oracle)
     return {"value": bytes_unique * frac / t / 1e9, "unit": "GB/s", "cores": cores,
+            "tiny_config_single_thread_us": tiny_us,
             "kind": "oracle",
             "sample": f"first {nreq} of {wl.B} requests ({nreq * per_req} of {wl.B * per_req} "
                       f"query rows), {len(times)} repeats, median {t:.3f} s wall each, "
                       f"{sum(times) * cores:.0f} core-seconds in total",
             "ms_per_step_extrapolated": t / frac * 1e3}
+
+
+def tiny_single_thread_us(oracle):
+    """The smallest benchmark configuration (B=1, beam 4, 4 heads of 64, 32 + 8 keys)
+    through the same oracle on ONE host thread: the OpenMP runtime is told to use
+    one thread for the call and its previous setting is restored."""
+    import ctypes
+    import numpy as np
+    from paper_2401_05391_amd.workloads import CONFIGS, make_inputs
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+    except OSError:
+        return None
+    wl = CONFIGS["tiny"]
+    x = make_inputs(wl)
+    rk, rv = x["resp_k"].copy(), x["resp_v"].copy()
+    oracle.append_kv(rk, rv, x["k_new"], x["v_new"], wl.T - 1)
+    before = oracle.num_threads()
+    gomp.omp_set_num_threads(1)
+    try:
+        times = []
+        for _ in range(20):
+            t0 = time.perf_counter()
+            oracle.sdpa_decode(x["q"], x["prompt_k"], x["prompt_v"], rk, rv, x["parent"], wl.W, wl.T,
+                               wl.scale, slopes=x["slopes"])
+            times.append(time.perf_counter() - t0)
+    finally:
+        gomp.omp_set_num_threads(before)
+    return float(np.median(times)) * 1e6
 
 
 MFMA_F16_PEAK_TFLOPS = 2500.0     # MI355X published dense fp16 matrix-core peak
