@@ -55,7 +55,9 @@ typedef enum {
     SEGKV_UNSUPPORTED = -2,         /* D or beam outside the compiled variants                */
     SEGKV_MISALIGNED = -3,          /* a tensor base is not 16-byte aligned                   */
     SEGKV_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes < segkv_workspace_bytes(d)             */
-    SEGKV_HIP_ERROR = -5            /* a launch was rejected by the HIP runtime               */
+    SEGKV_HIP_ERROR = -5,           /* a launch was rejected by the HIP runtime               */
+    SEGKV_STATIC_SCRATCH_EXCEEDED = -6 /* segkv_sdpa_decode_static_scratch only: the dimensions
+                                       need more than SEGKV_STATIC_SCRATCH_BYTES of scratch   */
 } segkv_status;
 
 /*
@@ -228,6 +230,37 @@ int segkv_sdpa_decode_lineage(void* out, const void* q,
                               const int32_t* prompt_lens,
                               void* workspace, size_t workspace_bytes,
                               float scale, const segkv_dims* d, void* stream);
+
+/*
+ * segkv_sdpa_decode for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, kernels, arithmetic and results as
+ * segkv_sdpa_decode, without `workspace`: the split-KV partial results go to a
+ * buffer of SEGKV_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (one copy on every GPU the library runs on, held until the process
+ * ends).  The call allocates and frees nothing, on the host side of the HIP
+ * runtime or through it.
+ *   - Dimensions whose segkv_workspace_bytes(d) exceeds SEGKV_STATIC_SCRATCH_BYTES
+ *     are rejected with SEGKV_STATIC_SCRATCH_EXCEEDED before anything is enqueued
+ *     (the check is host arithmetic and needs no device).
+ *   - The buffer's address is looked up once per device, on the first call made
+ *     with that device current that needs scratch; make that call outside graph
+ *     capture.  SEGKV_HIP_ERROR if the lookup fails.
+ *   - Every call on a GPU uses that GPU's one buffer, which keeps the previous
+ *     call's contents (none of them is read before it is overwritten).  Calls
+ *     that overlap in time on one GPU -- different streams, or graphs replayed
+ *     concurrently -- race on it: serialise them, or use segkv_sdpa_decode with
+ *     a workspace per stream.
+ */
+#define SEGKV_STATIC_SCRATCH_BYTES (16u << 20)
+int segkv_sdpa_decode_static_scratch(void* out, const void* q,
+                                     const void* prompt_k, const void* prompt_v,
+                                     void* resp_k, void* resp_v,
+                                     const int32_t* parent,
+                                     const void* k_new, const void* v_new,
+                                     const float* alibi_slopes,
+                                     int32_t* anc_out,
+                                     float scale, const segkv_dims* d, void* stream);
 
 /* Bytes of device scratch segkv_sdpa_decode needs for these dimensions (the
  * split-KV partial results of Section 3.3's accumulate step).  0 on invalid

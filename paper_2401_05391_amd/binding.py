@@ -20,13 +20,16 @@ SEGKV_UNSUPPORTED = -2
 SEGKV_MISALIGNED = -3
 SEGKV_WORKSPACE_TOO_SMALL = -4
 SEGKV_HIP_ERROR = -5
+SEGKV_STATIC_SCRATCH_EXCEEDED = -6
+STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_status_string", "segkv_stream_read_probe", "segkv_cache_token_bytes",
            "segkv_cache_standard_bytes", "segkv_cache_segment_bytes", "segkv_response_capacity",
            "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
            "segkv_rope_append", "segkv_sdpa_decode_ragged", "segkv_sdpa_decode_seq_first_prompt",
-           "segkv_lineage_bytes", "segkv_lineage_update", "segkv_sdpa_decode_lineage")
+           "segkv_lineage_bytes", "segkv_lineage_update", "segkv_sdpa_decode_lineage",
+           "segkv_sdpa_decode_static_scratch")
 
 
 class SegkvDims(ctypes.Structure):
@@ -61,6 +64,9 @@ def load_library():
     lib.segkv_sdpa_decode.restype = ctypes.c_int
     lib.segkv_sdpa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                                       ctypes.c_float, dp, vp]
+    lib.segkv_sdpa_decode_static_scratch.restype = ctypes.c_int
+    lib.segkv_sdpa_decode_static_scratch.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                     ctypes.c_float, dp, vp]
     lib.segkv_sdpa_decode_ragged.restype = ctypes.c_int
     lib.segkv_sdpa_decode_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                                              ctypes.c_float, dp, vp]
@@ -157,6 +163,18 @@ def sdpa_decode(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvD
         _ptr(workspace), ws_bytes, float(scale), ctypes.byref(dims), _stream_handle(stream))
     if rc != SEGKV_OK:
         raise SegkvError(rc, "segkv_sdpa_decode")
+
+
+def sdpa_decode_static_scratch(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, dims: SegkvDims,
+                               scale: float, k_new=None, v_new=None, alibi_slopes=None,
+                               anc_out=None, stream=None) -> None:
+    """sdpa_decode without a workspace argument: partials go to the library's static buffer."""
+    rc = load_library().segkv_sdpa_decode_static_scratch(
+        _ptr(out), _ptr(q), _ptr(prompt_k), _ptr(prompt_v), _ptr(resp_k), _ptr(resp_v),
+        _ptr(parent), _ptr(k_new), _ptr(v_new), _ptr(alibi_slopes), _ptr(anc_out),
+        float(scale), ctypes.byref(dims), _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_sdpa_decode_static_scratch")
 
 
 def sdpa_decode_ragged(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, prompt_lens,

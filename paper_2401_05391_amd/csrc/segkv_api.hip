@@ -2,14 +2,37 @@
 // Declarations and the full contract are in include/segkv.h.
 #include "segkv.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 
 #include "segkv_launch.h"
 
+// Scratch of segkv_sdpa_decode_static_scratch: one copy per GPU the library runs
+// on, held until the process ends.  The name is a host-side stand-in, not a
+// device address: host code only ever uses the pointer hipGetSymbolAddress
+// returns for the current device (static_scratch_ptr below).
+static __device__ __align__(256) unsigned char scratch[SEGKV_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using segkv::SdpaParams;
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+// Allocates nothing.  Null on failure.
+void* static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr) return ptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // a racing thread stores the same value
+    return ptr;
+}
 
 struct Plan {
     int G, nq, QB, n_qblocks;
@@ -226,6 +249,8 @@ const char* segkv_status_string(int status)
         case SEGKV_MISALIGNED: return "tensor pointer is not 16-byte aligned";
         case SEGKV_WORKSPACE_TOO_SMALL: return "workspace too small";
         case SEGKV_HIP_ERROR: return "HIP runtime rejected a kernel launch";
+        case SEGKV_STATIC_SCRATCH_EXCEEDED:
+            return "these dimensions need more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -370,6 +395,29 @@ int segkv_sdpa_decode_ragged(void* out, const void* q, const void* prompt_k, con
     return sdpa_decode_impl(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new, v_new,
                             alibi_slopes, prompt_lens, false, anc_out, workspace, workspace_bytes,
                             scale, d, stream);
+}
+
+int segkv_sdpa_decode_static_scratch(void* out, const void* q, const void* prompt_k,
+                                     const void* prompt_v, void* resp_k, void* resp_v,
+                                     const int32_t* parent, const void* k_new, const void* v_new,
+                                     const float* alibi_slopes, int32_t* anc_out, float scale,
+                                     const segkv_dims* d, void* stream)
+{
+    if (!dims_ok(d)) return SEGKV_INVALID_ARG;
+    if (!dims_supported(d)) return SEGKV_UNSUPPORTED;
+    // the size check comes before anything touches the device
+    const Plan pl = make_plan(d);
+    const size_t need = pl.ws_ml_bytes + pl.ws_acc_bytes;
+    if (need > (size_t)SEGKV_STATIC_SCRATCH_BYTES) return SEGKV_STATIC_SCRATCH_EXCEEDED;
+    void* ptr = nullptr;
+    if (need > 0) {
+        ptr = static_scratch_ptr();
+        if (!ptr) return SEGKV_HIP_ERROR;
+    }
+    // The partials need no clearing: every chunk's work-group writes its whole
+    // slice before the merge pass reads it.
+    return sdpa_decode_impl(out, q, prompt_k, prompt_v, resp_k, resp_v, parent, k_new, v_new,
+                            alibi_slopes, nullptr, false, anc_out, ptr, need, scale, d, stream);
 }
 
 int segkv_sdpa_decode_lineage(void* out, const void* q, const void* prompt_k, const void* prompt_v,

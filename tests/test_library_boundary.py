@@ -36,8 +36,8 @@ def test_dims_struct_matches_header():
 
 def test_status_strings():
     assert segkv.status_string(0) == "ok"
-    seen = {segkv.status_string(c) for c in range(-5, 1)}
-    assert len(seen) == 6
+    seen = {segkv.status_string(c) for c in range(-6, 1)}
+    assert len(seen) == 7
     assert segkv.status_string(-99) == "unknown status"
 
 
@@ -78,6 +78,25 @@ def test_workspace_requirement_is_enforced(monkeypatch):
     assert _decode(d, ws=None, ws_bytes=need) == binding.SEGKV_WORKSPACE_TOO_SMALL
     assert segkv.workspace_bytes(segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=96, Lp=512, T=5,
                                                  Tcap=16)) == 0
+
+
+def test_static_scratch_entry_point_rejects_oversized_dimensions_without_a_device():
+    lib = segkv.load_library()
+    call = lambda d_, out=FAKE: lib.segkv_sdpa_decode_static_scratch(
+        out, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, None, 0.125, ctypes.byref(d_), None)
+    # a response of several chunks over a large batch: 7 partials of 8192 x 128 floats
+    big = segkv.make_dims(B=64, beam=4, Hq=32, Hkv=32, D=128, Lp=1024, T=1300, Tcap=1312)
+    assert segkv.workspace_bytes(big) > binding.STATIC_SCRATCH_BYTES
+    assert call(big) == binding.SEGKV_STATIC_SCRATCH_EXCEEDED
+    assert "static buffer" in segkv.status_string(binding.SEGKV_STATIC_SCRATCH_EXCEEDED)
+    header = open(os.path.join(ROOT, "include", "segkv.h")).read()
+    assert re.search(r"#define SEGKV_STATIC_SCRATCH_BYTES \(16u << 20\)", header)
+    assert binding.STATIC_SCRATCH_BYTES == 16 << 20
+    # argument checks come first, as in segkv_sdpa_decode
+    ok = segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=64, T=5, Tcap=16)
+    assert call(ok, out=None) == binding.SEGKV_INVALID_ARG
+    assert call(segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=96, Lp=64, T=5, Tcap=16)) == binding.SEGKV_UNSUPPORTED
+    assert call(segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=64, T=0, Tcap=16)) == binding.SEGKV_INVALID_ARG
 
 
 def test_append_rejects_bad_arguments_without_a_device():
