@@ -9,7 +9,15 @@ keep every launch HBM-cold the timed loop cycles through several independent
 buffer sets ("layers") whose total footprint exceeds 4x the 256 MB Infinity
 Cache, as a real model cycles through its layers' caches.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+One clock: a pair of HIP events on the launch stream around the whole timed
+region (at least --steps launches, and as many as it takes to fill 50 ms, so
+that 50 us kernels are not timed over a millisecond); `value`, `ms_per_step`
+and `roofline.achieved` all come from it.  The host's wall clock over the same
+region and a per-launch event-pair spread are reported beside it.
+
+Prints ONE JSON line (see README / DESIGN for the fields); besides the headline
+workload it carries the other benchmark configurations, the paper's Figure 6
+batch-size sweep in both prompt layouts, and the prefill attention shapes.
 """
 from __future__ import annotations
 
@@ -27,15 +35,22 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 MALL_BYTES = 256 << 20
 
-# HBM bytes per launch of the decode kernel, measured with rocprofv3
-# (FETCH_SIZE + WRITE_SIZE, each scaled by a copy kernel of known size); the
-# figures and the commands behind them are in profiles/sdpa_decode_*.md.
-MEASURED_TRAFFIC_BYTES = {
-    "llama2_7b_greedy": 2420526757,
-    "llama2_70b_gqa": 309481562,
-    "gptj6b": 307540819,
-    "bloom176b_alibi": 537476744,
+# HBM bytes per launch of the decode kernel as rocprofv3 counted them (FETCH_SIZE +
+# WRITE_SIZE, each scaled by a copy kernel of known size).  Not measured by this
+# script: every figure names the summary under profiles/ that holds it and the
+# commit whose kernel was profiled; a kernel changed since then needs a new profile.
+PROFILED_TRAFFIC = {
+    "llama2_7b_greedy": {"bytes": 2420526757, "profile": "profiles/sdpa_decode_mfma_llama2_7b_greedy.md",
+                         "kernel_commit": "f7eddc9"},
+    "llama2_70b_gqa": {"bytes": 309481562, "profile": "profiles/sdpa_decode_mfma_llama2_70b_gqa.md",
+                       "kernel_commit": "f7eddc9"},
+    "gptj6b": {"bytes": 307540819, "profile": "profiles/sdpa_decode_mfma_gptj6b.md",
+               "kernel_commit": "f7eddc9"},
+    "bloom176b_alibi": {"bytes": 537476744, "profile": "profiles/sdpa_decode_mfma_bloom176b_alibi.md",
+                        "kernel_commit": "f7eddc9"},
 }
+MIN_TIMED_REGION_S = 0.05      # short kernels are launched often enough to fill this
+MAX_TIMED_LAUNCHES = 4000
 
 
 def algorithmic_bytes(wl, unique_rows: int) -> dict:
@@ -106,10 +121,45 @@ class DeviceSet:
                 "parent": c(self.parent), "slopes": c(self.slopes)}
 
 
-def unique_rows_from_anc(anc, wl):
+def distinct_response_rows(parent, B, W):
+    """Bookkeeping for the byte count: how many distinct (step, slot) response rows the
+    beams of all requests descend from.  Walks the parent table backwards from the last
+    step (slot of beam j at step T-1 is j; one step earlier it is parent[s][slot])."""
     import numpy as np
-    offs = (np.arange(wl.N) // wl.W) * wl.W
-    return int(sum(np.unique(offs + anc[s]).size for s in range(wl.T)))
+    T = parent.shape[0]
+    base = (np.arange(B * W) // W) * W
+    slot = np.arange(B * W) % W
+    total = 0
+    for s in range(T - 1, -1, -1):
+        total += np.unique(base + slot).size
+        if s > 0:
+            slot = parent[s][base + slot]
+    return int(total)
+
+
+def timed_region(call_list, n_launches, torch):
+    """n_launches calls (cycling through call_list) between ONE pair of HIP events on the
+    launch stream, bracketed by synchronisations.  Returns (event seconds, wall seconds)."""
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    k = len(call_list)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(n_launches):
+        call_list[i % k]()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return e0.elapsed_time(e1) * 1e-3, wall
+
+
+def launches_for(call_list, steps, torch):
+    """At least `steps` launches, and enough of them that the timed region lasts
+    MIN_TIMED_REGION_S (estimated from a short burst)."""
+    ev_s, _ = timed_region(call_list, 10, torch)
+    per = max(ev_s / 10, 1e-7)
+    return int(min(MAX_TIMED_LAUNCHES, max(steps, math.ceil(MIN_TIMED_REGION_S / per))))
 
 
 def build_lineage(wl, parent_np, segkv, torch):
@@ -126,7 +176,7 @@ def build_lineage(wl, parent_np, segkv, torch):
 
 
 def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_seconds,
-                  prompt_seq_first=False, use_lineage=False):
+                  prompt_seq_first=False, use_lineage=False, probe=True):
     import numpy as np
     from paper_2401_05391_amd.workloads import alibi_slopes, make_parent
 
@@ -143,54 +193,50 @@ def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_second
             for i in range(n_sets)]
     torch.cuda.synchronize()
 
-    # resolved ancestors as the kernel used them -> distinct response rows referenced
-    anc = torch.empty(wl.T, wl.N, dtype=torch.int32, device="cuda:0")
     s0 = sets[0]
     cpu_inputs = s0.to_numpy() if want_cpu_baseline else None
-    entry = segkv.sdpa_decode_seq_first_prompt if prompt_seq_first else segkv.sdpa_decode
-    entry(s0.out, s0.q, s0.pk, s0.pv, s0.rk, s0.rv, s0.parent, s0.dims, wl.scale,
-          k_new=s0.kn, v_new=s0.vn, alibi_slopes=s0.slopes, anc_out=anc, workspace=s0.ws)
-    torch.cuda.synchronize()
-    U = unique_rows_from_anc(anc.cpu().numpy(), wl)
+    U = distinct_response_rows(parent_np, wl.B, wl.W)
     nbytes = algorithmic_bytes(wl, U)
+    calls = [st.call for st in sets]
 
     for i in range(warmup):
-        sets[i % n_sets].call()
+        calls[i % n_sets]()
     torch.cuda.synchronize()
 
-    # (1) whole-job wall clock over exactly `steps` steps
-    t0 = time.perf_counter()
-    for i in range(steps):
-        sets[i % n_sets].call()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / steps
+    # (1) THE clock: HIP events on the launch stream around the whole timed region.
+    # `steps` launches at least; short kernels get more, so that the region lasts
+    # MIN_TIMED_REGION_S and the events' own cost (a few us) disappears in it.
+    n_launches = launches_for(calls, steps, torch)
+    ev_s, wall_s = timed_region(calls, n_launches, torch)
+    ms_per_step = ev_s * 1e3 / n_launches
 
-    # (2) per-launch device time with HIP events on the launch stream
+    # (2) beside it: one event pair per launch (adds 1-3 us to every launch: the pair's
+    # own records sit between the kernels), for the spread only
+    n_pairs = min(n_launches, 400)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in range(steps)]
-    for i in range(steps):
+           for _ in range(n_pairs)]
+    for i in range(n_pairs):
         evs[i][0].record()
-        sets[i % n_sets].call()
+        calls[i % n_sets]()
         evs[i][1].record()
     torch.cuda.synchronize()
     dev_ms = np.array([a.elapsed_time(b) for a, b in evs])
 
     # (3) practical streaming-read ceiling: same bytes, pure 128-bit loads
-    sink = torch.empty(4096, dtype=torch.int32, device="cuda:0")
-    probe_src = [torch.cat([s.pk.view(-1), s.pv.view(-1)]) for s in sets[:2]]
-    for i in range(3):
-        segkv.stream_read_probe(probe_src[i % 2], sink)
-    pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
-    for i in range(10):
-        pe[i][0].record()
-        segkv.stream_read_probe(probe_src[i % 2], sink)
-        pe[i][1].record()
-    torch.cuda.synchronize()
-    probe_ms = float(np.median([a.elapsed_time(b) for a, b in pe]))
-    probe_gbs = probe_src[0].numel() * 2 / (probe_ms * 1e-3) / 1e9
-    del probe_src
+    probe_gbs = None
+    if probe and wl.Lp > 0:
+        sink = torch.empty(4096, dtype=torch.int32, device="cuda:0")
+        probe_src = [torch.cat([s.pk.view(-1), s.pv.view(-1)]) for s in sets[:2]]
+        probe_calls = [lambda i=i: segkv.stream_read_probe(probe_src[i], sink) for i in range(2)]
+        for i in range(3):
+            probe_calls[i % 2]()
+        n_probe = launches_for(probe_calls, 10, torch) // 4 + 10
+        probe_s, _ = timed_region(probe_calls, n_probe, torch)
+        probe_gbs = probe_src[0].numel() * 2 / (probe_s / n_probe) / 1e9
+        del probe_src, probe_calls
 
+    gbs = nbytes["unique"] / (ms_per_step * 1e-3) / 1e9
+    prof = PROFILED_TRAFFIC.get(wl.name)
     res = {
         "workload": wl.name,
         "shape": {"B": wl.B, "beam": wl.W, "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "Lp": wl.Lp,
@@ -198,20 +244,26 @@ def time_workload(wl, steps, warmup, segkv, torch, want_cpu_baseline, cpu_second
         "buffer_sets": n_sets,
         "unique_response_rows": U,
         "bytes_unique": nbytes["unique"], "bytes_nominal": nbytes["nominal"],
+        "timed_launches": n_launches,
+        "clock": "HIP events on the launch stream around the timed region of timed_launches launches",
         "ms_per_step": ms_per_step,
         "us_per_layer_step": ms_per_step * 1e3,
-        "gbs_unique": nbytes["unique"] / (ms_per_step * 1e-3) / 1e9,
+        "wall_clock_us_per_layer_step": wall_s * 1e6 / n_launches,
+        "gbs_unique": gbs,
         "gbs_nominal": nbytes["nominal"] / (ms_per_step * 1e-3) / 1e9,
-        "device_us": {"mean": float(dev_ms.mean() * 1e3), "median": float(np.median(dev_ms) * 1e3),
-                      "min": float(dev_ms.min() * 1e3), "p90": float(np.percentile(dev_ms, 90) * 1e3)},
+        "per_launch_event_pairs_us": {
+            "n": n_pairs, "mean": float(dev_ms.mean() * 1e3), "median": float(np.median(dev_ms) * 1e3),
+            "min": float(dev_ms.min() * 1e3), "p90": float(np.percentile(dev_ms, 90) * 1e3)},
         "stream_read_probe_gbs": probe_gbs,
         "workspace_bytes": segkv.workspace_bytes(s0.dims),
     }
     res["roofline"] = {
-        "bound": "hbm", "achieved": nbytes["unique"] / (dev_ms.mean() * 1e-3) / 1e9,
-        "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": nbytes["unique"] / (dev_ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+        "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": gbs / HBM_PEAK_GBS,
+        "traffic": prof["bytes"] if prof else None,
+        "traffic_source": ({"profile": prof["profile"], "kernel_commit": prof["kernel_commit"],
+                            "note": "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, not measured in this run"}
+                           if prof else None),
     }
 
     if want_cpu_baseline:
@@ -232,6 +284,11 @@ def cpu_baseline(wl, x, bytes_unique, budget_s, U):
     oracle.append_kv(rk, rv, x["k_new"], x["v_new"], wl.T - 1)
     per_req = wl.W * wl.Hq
     cores = oracle.num_threads()
+    # the byte count's distinct-row figure against the oracle's own ancestor table
+    anc = oracle.ancestors(x["parent"], wl.B, wl.W)
+    offs = (np.arange(wl.N) // wl.W) * wl.W
+    U_oracle = int(sum(np.unique(offs + anc[s]).size for s in range(wl.T)))
+    assert U_oracle == U, f"distinct response rows: {U} counted here, {U_oracle} by the oracle"
 
     def run(nreq):
         pairs = np.array([(n, h) for n in range(nreq * wl.W) for h in range(wl.Hq)], dtype=np.int32)
@@ -252,6 +309,7 @@ def cpu_baseline(wl, x, bytes_unique, budget_s, U):
     return {"value": bytes_unique * frac / t / 1e9, "unit": "GB/s", "cores": cores,
             "tiny_config_single_thread_us": tiny_us,
             "kind": "oracle",
+            "unique_response_rows_by_oracle": U_oracle,
             "sample": f"first {nreq} of {wl.B} requests ({nreq * per_req} of {wl.B * per_req} "
                       f"query rows), {len(times)} repeats, median {t:.3f} s wall each, "
                       f"{sum(times) * cores:.0f} core-seconds in total",
@@ -298,8 +356,10 @@ PREFILL_SHAPES = [
 ]
 
 
-def prefill_bench(steps, warmup, segkv, torch):
-    """Causal prefill attention: 4 * B * Hq * D * N0 (N0 + 1) / 2 flops per call."""
+def prefill_rows(steps, warmup, segkv, torch):
+    """Causal prefill attention on the prompt shapes of the benchmark models:
+    4 * B * Hq * D * N0 (N0 + 1) / 2 flops per call, timed like the decode step
+    (one HIP-event pair around the timed region)."""
     dev = torch.device("cuda:0")
     rows = []
     for name, B, N0, Hq, Hkv, D in PREFILL_SHAPES:
@@ -309,35 +369,54 @@ def prefill_bench(steps, warmup, segkv, torch):
         q, k, v = rnd(B, N0, Hq, D), rnd(B, N0, Hkv, D), rnd(B, N0, Hkv, D)
         out = torch.empty_like(q)
         dims = segkv.make_dims(B, 1, Hq, Hkv, D, N0, 1, 1)
+        call = [lambda: segkv.sdpa_prefill(out, q, k, v, dims, D ** -0.5)]
         for _ in range(warmup):
-            segkv.sdpa_prefill(out, q, k, v, dims, D ** -0.5)
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in range(steps)]
-        t0 = time.perf_counter()
-        for e0, e1 in evs:
-            e0.record()
-            segkv.sdpa_prefill(out, q, k, v, dims, D ** -0.5)
-            e1.record()
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-        dev_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+            call[0]()
+        n = launches_for(call, steps, torch)
+        ev_s, wall_s = timed_region(call, n, torch)
         flops = 4.0 * B * Hq * D * N0 * (N0 + 1) / 2
+        tflops = flops / (ev_s / n) / 1e12
         rows.append({"workload": name, "shape": {"B": B, "N0": N0, "Hq": Hq, "Hkv": Hkv, "D": D},
-                     "ms_per_step": wall_ms, "device_us_mean": dev_ms * 1e3, "flops": flops,
-                     "tflops": flops / (dev_ms * 1e-3) / 1e12,
-                     "tokens_per_s": B * N0 / (wall_ms * 1e-3)})
+                     "timed_launches": n, "ms_per_step": ev_s * 1e3 / n,
+                     "wall_clock_ms_per_step": wall_s * 1e3 / n, "flops": flops, "tflops": tflops,
+                     "tokens_per_s": B * N0 / (ev_s / n),
+                     "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_F16_PEAK_TFLOPS,
+                                  "unit": "TFLOP/s", "frac": tflops / MFMA_F16_PEAK_TFLOPS,
+                                  "traffic": None}})
         del q, k, v, out
+    return rows
+
+
+def prefill_bench(steps, warmup, segkv, torch):
+    rows = prefill_rows(steps, warmup, segkv, torch)
     head = rows[0]
     return {"metric": "prefill causal SDPA (segkv_sdpa_prefill): achieved fp16 TFLOP/s",
             "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
             "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "f16", "data": "synthetic",
             "config": {"workload": head["workload"], **head["shape"]},
-            "roofline": {"bound": "mfma", "achieved": head["tflops"], "peak": MFMA_F16_PEAK_TFLOPS,
-                         "unit": "TFLOP/s", "frac": head["tflops"] / MFMA_F16_PEAK_TFLOPS,
-                         "traffic": None},
-            "cpu_baseline": None, "shapes": rows}
+            "roofline": head["roofline"], "cpu_baseline": None, "shapes": rows}
+
+
+def fig6_rows(steps, warmup, segkv, torch):
+    """Section 4.1, Figure 6: Llama2-13B attention shape, beam 4, 1024 prompt / 128
+    response tokens, batch size 1..64, with the prompt segment stored batch first
+    (the paper's choice) and sequence first (the other arm of its comparison)."""
+    from paper_2401_05391_amd.workloads import FIG6_BATCH_SIZES, fig6_workload
+    rows = []
+    for bs in FIG6_BATCH_SIZES:
+        r = time_workload(fig6_workload(bs), steps, warmup, segkv, torch, False, 0, probe=False)
+        r2 = time_workload(fig6_workload(bs), steps, warmup, segkv, torch, False, 0,
+                           prompt_seq_first=True, probe=False)
+        rows.append({"batch_size": bs, "timed_launches": r["timed_launches"],
+                     "us_per_layer_step": r["us_per_layer_step"],
+                     "seq_first_prompt_us_per_layer_step": r2["us_per_layer_step"],
+                     "bytes_unique": r["bytes_unique"], "bytes_nominal": r["bytes_nominal"],
+                     "gbs_unique": r["gbs_unique"], "gbs_nominal": r["gbs_nominal"],
+                     "seq_first_prompt_gbs_unique": r2["gbs_unique"],
+                     "roofline": {k: r["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac")},
+                     "seq_first_prompt_roofline_frac": r2["roofline"]["frac"]})
+    return rows
 
 
 def run_counter_calibration(segkv, torch):
@@ -432,6 +511,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=20.0,
                     help="CPU-core-seconds to spend on the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the fig6 (Figure 6 batch-size sweep, both prompt layouts) and prefill "
+                         "sub-records of the default line")
     ap.add_argument("--fig6-sweep", action="store_true",
                     help="instead of the headline workload, time the paper's Figure 6 experiment "
                          "(Llama2-13B attention shape, beam 4, 1024/128 tokens, batch size 1..64) and "
@@ -475,20 +557,7 @@ def main():
         return
 
     if a.fig6_sweep:
-        from paper_2401_05391_amd.workloads import FIG6_BATCH_SIZES, fig6_workload
-        rows = []
-        for bs in FIG6_BATCH_SIZES:
-            r = time_workload(fig6_workload(bs), a.steps, a.warmup, segkv, torch, False, 0)
-            # the figure's second curve: the prompt segment stored sequence first
-            r2 = time_workload(fig6_workload(bs), a.steps, a.warmup, segkv, torch, False, 0,
-                               prompt_seq_first=True)
-            rows.append({"batch_size": bs, "us_per_layer_step": r["us_per_layer_step"],
-                         "seq_first_prompt_device_us_mean": r2["device_us"]["mean"],
-                         "seq_first_prompt_gbs_unique": r2["gbs_unique"],
-                         "device_us_mean": r["device_us"]["mean"], "bytes_unique": r["bytes_unique"],
-                         "bytes_nominal": r["bytes_nominal"], "gbs_unique": r["gbs_unique"],
-                         "gbs_nominal": r["gbs_nominal"], "frac_of_peak": r["roofline"]["frac"],
-                         "stream_read_probe_gbs": r["stream_read_probe_gbs"]})
+        rows = fig6_rows(a.steps, a.warmup, segkv, torch)
         last = rows[-1]
         print(json.dumps({
             "metric": "fused segment-KV decode SDPA: achieved HBM GB/s, Figure 6 batch-size sweep",
@@ -498,7 +567,7 @@ def main():
             "data": "synthetic",
             "config": {"workload": "fig6_llama2_13b_sweep", "beam": 4, "Hq": 40, "Hkv": 40, "D": 128,
                        "Lp": 1024, "T": 128, "value_is_batch_size": last["batch_size"]},
-            "sweep": rows}), flush=True)
+            "roofline": last["roofline"], "sweep": rows}), flush=True)
         return
 
     wl = CONFIGS[a.workload]
@@ -508,6 +577,11 @@ def main():
     for name in [n for n in a.others.split(",") if n and n != a.workload]:
         others.append(time_workload(CONFIGS[name], a.steps, a.warmup, segkv, torch, False, 0,
                                     use_lineage=a.lineage))
+
+    # the rows next to the path: the paper's Figure 6 sweep (both prompt layouts) and the
+    # prefill attention, each timed the same way, each with its own roofline
+    fig6 = None if a.no_extras else fig6_rows(a.steps, a.warmup, segkv, torch)
+    prefill = None if a.no_extras else prefill_rows(max(a.steps // 4, 10), a.warmup, segkv, torch)
 
     calibration = None
     if a.calibrate_counters:
@@ -520,6 +594,8 @@ def main():
         "ms_per_step": main_res["ms_per_step"], "us_per_layer_step": main_res["us_per_layer_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
+        "timed_launches": main_res["timed_launches"], "clock": main_res["clock"],
+        "wall_clock_us_per_layer_step": main_res["wall_clock_us_per_layer_step"],
         "config": {"workload": wl.name, **main_res["shape"], "append": "fused",
                    "beam_lineage": "list kept across steps" if a.lineage else "parent table",
                    "buffer_sets": main_res["buffer_sets"]},
@@ -527,13 +603,23 @@ def main():
         "roofline": main_res["roofline"],
         "cpu_baseline": main_res.get("cpu_baseline"),
         "detail": {k: main_res[k] for k in ("bytes_unique", "bytes_nominal", "unique_response_rows",
-                                            "gbs_nominal", "device_us", "stream_read_probe_gbs",
-                                            "workspace_bytes")},
+                                            "gbs_nominal", "per_launch_event_pairs_us",
+                                            "stream_read_probe_gbs", "workspace_bytes")},
         "counter_calibration": calibration,
-        "other_workloads": [{k: r[k] for k in ("workload", "shape", "us_per_layer_step", "gbs_unique",
-                                               "gbs_nominal", "bytes_unique", "device_us", "roofline",
+        "other_workloads": [{k: r[k] for k in ("workload", "shape", "timed_launches", "us_per_layer_step",
+                                               "wall_clock_us_per_layer_step", "gbs_unique",
+                                               "gbs_nominal", "bytes_unique", "unique_response_rows",
+                                               "per_launch_event_pairs_us", "roofline",
                                                "stream_read_probe_gbs", "buffer_sets")}
                             for r in others],
+        "fig6": None if fig6 is None else {
+            "what": "Section 4.1, Figure 6: Llama2-13B attention shape (40 heads of 128), beam 4, 1024 "
+                    "prompt / 128 response tokens; prompt segment batch first and sequence first",
+            "sweep": fig6},
+        "prefill": None if prefill is None else {
+            "what": "segkv_sdpa_prefill (causal prompt attention, Section 3.3's special case) on the "
+                    "prompt shapes of the benchmark models; roofline: fp16 dense MFMA",
+            "shapes": prefill},
     }
     print(json.dumps(line), flush=True)
 

@@ -281,8 +281,25 @@ size_t segkv_workspace_bytes(const segkv_dims* d);
  */
 size_t segkv_value_stagger_bytes(const segkv_dims* d);
 
-/* Static, human-readable text for a status code. */
+/* Human-readable text for a status code.  Static strings, except for
+ * SEGKV_HIP_ERROR, whose text ends with the HIP runtime's own description of
+ * the error that the calling thread's most recent rejected launch returned
+ * (hipGetErrorString); that one is kept per thread and stays valid until the
+ * thread's next segkv_status_string(SEGKV_HIP_ERROR). */
 const char* segkv_status_string(int status);
+
+/*
+ * TEST-ONLY.  The launch planner can be overridden through environment
+ * variables so that tests and A/B measurements reach every kernel and plan on
+ * small inputs: SEGKV_PATH (alu | mfma), SEGKV_TARGET_GROUPS, SEGKV_MIN_PCHUNK,
+ * SEGKV_MFMA_WAVES (4 | 8), SEGKV_HEADS_PER_WAVE (1 | 2 | 4), SEGKV_PAIR_HEADS
+ * (0 | 1), SEGKV_PREFILL (regs).  They are read ONCE, on the library's first
+ * use in the process, so that the workspace size a caller asked for and the
+ * launch that follows always agree; this call reads them again.  Not for use
+ * while other threads are inside the library.  Results never depend on the
+ * overrides beyond rounding order; production callers set none of them.
+ */
+void segkv_reload_tuning(void);
 
 /*
  * Prefill-phase attention (Section 3.1, prefill phase; Section 3.3: the special

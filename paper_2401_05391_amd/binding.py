@@ -29,7 +29,7 @@ EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
            "segkv_rope_append", "segkv_sdpa_decode_ragged", "segkv_sdpa_decode_seq_first_prompt",
            "segkv_lineage_bytes", "segkv_lineage_update", "segkv_sdpa_decode_lineage",
-           "segkv_sdpa_decode_static_scratch")
+           "segkv_sdpa_decode_static_scratch", "segkv_reload_tuning")
 
 
 class SegkvDims(ctypes.Structure):
@@ -67,6 +67,8 @@ def load_library():
     lib.segkv_sdpa_decode_static_scratch.restype = ctypes.c_int
     lib.segkv_sdpa_decode_static_scratch.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                                      ctypes.c_float, dp, vp]
+    lib.segkv_reload_tuning.restype = None
+    lib.segkv_reload_tuning.argtypes = []
     lib.segkv_sdpa_decode_ragged.restype = ctypes.c_int
     lib.segkv_sdpa_decode_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                                              ctypes.c_float, dp, vp]

@@ -4,7 +4,9 @@
 
 #include <atomic>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
+#include <mutex>
 
 #include "segkv_launch.h"
 
@@ -46,12 +48,41 @@ struct Plan {
     unsigned grid;
 };
 
-int env_int(const char* name, int fallback)
+int env_int(const char* name)
 {
     const char* s = std::getenv(name);
-    if (!s || !*s) return fallback;
+    if (!s || !*s) return 0;
     const long v = std::strtol(s, nullptr, 10);
-    return v > 0 ? (int)v : fallback;
+    return v > 0 ? (int)v : 0;
+}
+
+segkv::Tuning read_tuning_from_environment()
+{
+    segkv::Tuning t{};
+    const char* path = std::getenv("SEGKV_PATH");
+    t.path = (path && path[0] == 'a') ? 1 : (path && path[0] == 'm') ? 2 : 0;
+    const char* pair = std::getenv("SEGKV_PAIR_HEADS");
+    t.pair_heads = (pair && *pair) ? (pair[0] != '0' ? 1 : 0) : -1;
+    t.target_groups = env_int("SEGKV_TARGET_GROUPS");
+    t.min_pchunk = env_int("SEGKV_MIN_PCHUNK");
+    t.mfma_waves = env_int("SEGKV_MFMA_WAVES");
+    t.heads_per_wave = env_int("SEGKV_HEADS_PER_WAVE");
+    const char* prefill = std::getenv("SEGKV_PREFILL");
+    t.prefill_regs = (prefill && prefill[0] == 'r') ? 1 : 0;
+    return t;
+}
+
+std::mutex g_tuning_mutex;
+std::atomic<bool> g_tuning_ready{false};
+segkv::Tuning g_tuning;
+
+// Text of the last HIP error a launch of this thread returned (segkv_status_string).
+thread_local hipError_t t_last_hip_error = hipSuccess;
+inline int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return SEGKV_OK;
+    t_last_hip_error = e;
+    return SEGKV_HIP_ERROR;
 }
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -76,11 +107,10 @@ bool dims_supported(const segkv_dims* d)
 // against 14.9 us at batch 1, 27 against 31 us at batch 8, 90 against 98 us at
 // batch 31; the one exception found, D = 256 with one query per row and 128
 // units, is 5% the other way).  The vector-ALU kernel stays in the library as
-// the second implementation the tests compare: SEGKV_PATH=alu selects it.
+// the second implementation the tests compare (the test-only override selects it).
 bool want_mfma(int /*nq*/, long /*kv_units*/)
 {
-    const char* s = std::getenv("SEGKV_PATH");
-    return !(s && s[0] == 'a');
+    return segkv::tuning().path != 1;
 }
 
 // How the keys of one (request, KV head) unit are cut into work-groups.
@@ -94,15 +124,14 @@ bool want_mfma(int /*nq*/, long /*kv_units*/)
 // (the same bytes laid out as D = 128 stream 10-20% faster).  Pairing halves the
 // number of units, so it is only done when enough remain to fill the device:
 // measured faster from 384 (request, head) units up (+21% at 4096, +8% at 384 to
-// 1024), slower at 256 and below.  SEGKV_PAIR_HEADS=0 / 1 force the choice (A/B
-// measurements, tests).
+// 1024), slower at 256 and below.  The test-only override forces the choice.
 Plan make_plan(const segkv_dims* d_in)
 {
     Plan pl{};
     segkv_dims dd = *d_in;
-    const char* pair_env = std::getenv("SEGKV_PAIR_HEADS");
+    const segkv::Tuning& tune = segkv::tuning();
     const bool pair_possible = dd.D == 64 && dd.Hq == dd.Hkv && dd.Hkv % 2 == 0 && want_mfma(dd.beam, 0);
-    const bool pair_wanted = pair_env ? pair_env[0] != '0' : (long)dd.B * dd.Hkv >= 384;
+    const bool pair_wanted = tune.pair_heads >= 0 ? tune.pair_heads != 0 : (long)dd.B * dd.Hkv >= 384;
     pl.pair = (pair_possible && pair_wanted) ? 1 : 0;
     if (pl.pair) {
         dd.D = 128;
@@ -123,22 +152,22 @@ Plan make_plan(const segkv_dims* d_in)
         // of a unit, and always at D = 256 (accumulator registers)
         pl.QB = (pl.nq <= 16 || d->D == 256) ? 16 : 32;
         pl.HP = 1;
-        target_groups = env_int("SEGKV_TARGET_GROUPS", 256);
-        min_pchunk = env_int("SEGKV_MIN_PCHUNK", 256);   // one 32-key tile per wave
+        target_groups = tune.target_groups ? tune.target_groups : 256;
+        min_pchunk = tune.min_pchunk ? tune.min_pchunk : 256;   // one 32-key tile per wave
     } else {
         pl.QB = (pl.nq == 1) ? 1 : 4;
         // Adjacent KV heads per wave-wide load: 4 give 1 KB-contiguous reads,
         // the best streaming shape, but also 4x fewer, 4x longer units.  Keep at
         // least ~128 units; below that fall back to 2 or 1 heads per load
         // (measured: GPT-J shape fastest with 2, batch-1 shapes with 1).
-        const int hp_env = env_int("SEGKV_HEADS_PER_WAVE", 0);
+        const int hp_env = tune.heads_per_wave;
         pl.HP = hp_env ? hp_env : 4;
         while (pl.HP > 1 &&
                (d->Hkv % pl.HP != 0 || (pl.HP != 2 && pl.HP != 4) ||
                 (!hp_env && (long)d->B * (d->Hkv / pl.HP) * ceil_div(pl.nq, pl.QB) < 128)))
             pl.HP >>= 1;
-        target_groups = env_int("SEGKV_TARGET_GROUPS", 1024);
-        min_pchunk = env_int("SEGKV_MIN_PCHUNK", 64 * pl.QB);
+        target_groups = tune.target_groups ? tune.target_groups : 1024;
+        min_pchunk = tune.min_pchunk ? tune.min_pchunk : 64 * pl.QB;
     }
     pl.n_qblocks = ceil_div(pl.nq, pl.QB);
     const long units = (long)d->B * (d->Hkv / pl.HP) * pl.n_qblocks;
@@ -153,7 +182,7 @@ Plan make_plan(const segkv_dims* d_in)
         // group's start-up and merge then overlap the other's streaming.
         pl.NW = 8;
         const long kv_units = (long)d->B * d->Hkv * ceil_div(pl.nq, pl.QB);
-        const int nw_env = env_int("SEGKV_MFMA_WAVES", 0);
+        const int nw_env = tune.mfma_waves;
         if (pl.QB == 16 && d->D <= 128 &&
             (nw_env == 4 || (nw_env == 0 && kv_units > 256 &&
                              d->T * d->beam <=
@@ -238,7 +267,26 @@ bool lineage_ok(int32_t capacity, int32_t steps, const segkv_dims* d)
 
 }  // namespace
 
+namespace segkv {
+
+const Tuning& tuning()
+{
+    if (!g_tuning_ready.load(std::memory_order_acquire)) reload_tuning();
+    return g_tuning;
+}
+
+void reload_tuning()
+{
+    std::lock_guard<std::mutex> lock(g_tuning_mutex);
+    g_tuning = read_tuning_from_environment();
+    g_tuning_ready.store(true, std::memory_order_release);
+}
+
+}  // namespace segkv
+
 extern "C" {
+
+void segkv_reload_tuning(void) { segkv::reload_tuning(); }
 
 const char* segkv_status_string(int status)
 {
@@ -248,7 +296,14 @@ const char* segkv_status_string(int status)
         case SEGKV_UNSUPPORTED: return "unsupported head dimension or beam width";
         case SEGKV_MISALIGNED: return "tensor pointer is not 16-byte aligned";
         case SEGKV_WORKSPACE_TOO_SMALL: return "workspace too small";
-        case SEGKV_HIP_ERROR: return "HIP runtime rejected a kernel launch";
+        case SEGKV_HIP_ERROR: {
+            // the runtime's own text for the launch this thread last had rejected
+            static thread_local char text[160];
+            std::snprintf(text, sizeof text, "HIP runtime rejected a kernel launch: %s",
+                          t_last_hip_error == hipSuccess ? "no launch of this thread has failed"
+                                                         : hipGetErrorString(t_last_hip_error));
+            return text;
+        }
         case SEGKV_STATIC_SCRATCH_EXCEEDED:
             return "these dimensions need more scratch than the library's static buffer holds";
         default: return "unknown status";
@@ -283,7 +338,7 @@ int segkv_append_kv(void* resp_k, void* resp_v, const void* k_new, const void* v
     char* dk = (char*)resp_k + (size_t)t * row_bytes;
     char* dv = (char*)resp_v + (size_t)t * row_bytes;
     const hipError_t e = segkv::launch_append_kv(dk, dv, k_new, v_new, row_bytes, (hipStream_t)stream);
-    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+    return hip_status(e);
 }
 
 int segkv_sdpa_decode(void* out, const void* q, const void* prompt_k, const void* prompt_v,
@@ -366,20 +421,15 @@ int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void*
     p.rchunk = pl.rchunk;
     p.n_rchunks = pl.n_rchunks;
     p.resp_in_last = pl.resp_in_last;
-#ifdef SEGKV_TIMING
-    // tuning builds only: device buffer for per-wave phase timestamps, address in the environment
-    const char* timing_ptr = std::getenv("SEGKV_TIMING_PTR");
-    p.timing = timing_ptr ? (unsigned long long*)std::strtoull(timing_ptr, nullptr, 0) : nullptr;
-#endif
 
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, pl.D, pl.QB, pl.NW, pl.grid, st)
                            : segkv::launch_sdpa_decode(p, d->D, pl.QB, pl.HP, pl.grid, st);
-    if (e != hipSuccess) return SEGKV_HIP_ERROR;
+    if (e != hipSuccess) return hip_status(e);
     if (pl.n_chunks > 1) {
         e = segkv::launch_sdpa_merge(p.out, p.ws_ml, p.ws_acc, d->B * d->beam * d->Hq, d->D,
                                      pl.n_chunks, st);
-        if (e != hipSuccess) return SEGKV_HIP_ERROR;
+        if (e != hipSuccess) return hip_status(e);
     }
     return SEGKV_OK;
 }
@@ -412,7 +462,7 @@ int segkv_sdpa_decode_static_scratch(void* out, const void* q, const void* promp
     void* ptr = nullptr;
     if (need > 0) {
         ptr = static_scratch_ptr();
-        if (!ptr) return SEGKV_HIP_ERROR;
+        if (!ptr) return hip_status(hipErrorInvalidSymbol);
     }
     // The partials need no clearing: every chunk's work-group writes its whole
     // slice before the merge pass reads it.
@@ -447,7 +497,7 @@ int segkv_lineage_update(void* lineage, int32_t lineage_capacity, const int32_t*
     const hipError_t e = segkv::launch_lineage_update(
         (uint32_t*)lineage, parent_row, d->B, d->beam, t,
         segkv::kLineageHeaderWords + lineage_capacity, (hipStream_t)stream);
-    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+    return hip_status(e);
 }
 
 int segkv_sdpa_decode_seq_first_prompt(void* out, const void* q, const void* prompt_k,
@@ -490,7 +540,7 @@ int segkv_rope_append(void* q, const void* k_new, const void* v_new, void* resp_
     p.log2_base = std::log2((double)rope_base);
     const hipError_t e =
         segkv::launch_rope_append(p, interleaved ? 1 : 0, d->B * d->beam, (hipStream_t)stream);
-    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+    return hip_status(e);
 }
 
 int segkv_sdpa_prefill(void* out, const void* q, const void* k, const void* v,
@@ -513,7 +563,7 @@ int segkv_sdpa_prefill(void* out, const void* q, const void* k, const void* v,
     p.scale2 = scale * 1.4426950408889634f;
     p.B = d->B; p.N0 = d->Lp; p.Hq = d->Hq; p.Hkv = d->Hkv; p.G = d->Hq / d->Hkv;
     const hipError_t e = segkv::launch_sdpa_prefill(p, d->D, (hipStream_t)stream);
-    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+    return hip_status(e);
 }
 
 uint64_t segkv_cache_token_bytes(int32_t L, int32_t H, int32_t D, int32_t elem_bytes)
@@ -556,7 +606,7 @@ int segkv_grow_response(void* new_k, void* new_v, const void* old_k, const void*
     if (d->T == 0) return SEGKV_OK;
     const size_t bytes = (size_t)d->T * d->B * d->beam * d->Hkv * d->D * 2;
     const hipError_t e = segkv::launch_append_kv(new_k, new_v, old_k, old_v, bytes, (hipStream_t)stream);
-    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+    return hip_status(e);
 }
 
 int segkv_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream)
@@ -564,7 +614,7 @@ int segkv_stream_read_probe(const void* src, size_t bytes, void* sink, void* str
     if (!src || !sink || bytes == 0 || (bytes & 15u)) return SEGKV_INVALID_ARG;
     if (misaligned(src) || ((uintptr_t)sink & 3u)) return SEGKV_MISALIGNED;
     const hipError_t e = segkv::launch_stream_read_probe(src, bytes, sink, (hipStream_t)stream);
-    return e == hipSuccess ? SEGKV_OK : SEGKV_HIP_ERROR;
+    return hip_status(e);
 }
 
 }  // extern "C"

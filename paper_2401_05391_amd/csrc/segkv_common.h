@@ -20,6 +20,16 @@ constexpr float kEmptyMax = -1.0e30f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Between LDS writes of a wave and reads of the same locations by OTHER lanes of
+// the same wave: orders the two at wavefront scope for the compiler (the
+// hardware issues a wave's LDS operations in order).  Generates no instruction.
+__device__ __forceinline__ void wave_lds_exchange_point()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // ---- DPP lane exchange (all patterns used here read a valid lane) ----------
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float x)

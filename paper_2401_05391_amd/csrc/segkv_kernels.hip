@@ -498,8 +498,7 @@ __global__ __launch_bounds__(256) void stream_read_probe_kernel(const u32x4_t* _
 template <int D, int QB, int HP>
 static hipError_t launch_one(const SdpaParams& p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((sdpa_decode_alu_kernel<D, QB, HP>), dim3(grid), dim3(kThreads), 0, st, p);
-    return hipGetLastError();
+    return SEGKV_LAUNCH((sdpa_decode_alu_kernel<D, QB, HP>), dim3(grid), dim3(kThreads), st, p);
 }
 
 template <int D, int QB>
@@ -531,15 +530,13 @@ hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_
     const size_t threads = (size_t)NQ * (D / 4);
     const unsigned grid = (unsigned)((threads + 255) / 256);
     if (n_chunks <= 4)
-        hipLaunchKernelGGL(sdpa_merge_kernel<4>, dim3(grid), dim3(256), 0, st, out, ws_ml, ws_acc, NQ,
-                           D, n_chunks);
-    else if (n_chunks <= 8)
-        hipLaunchKernelGGL(sdpa_merge_kernel<8>, dim3(grid), dim3(256), 0, st, out, ws_ml, ws_acc, NQ,
-                           D, n_chunks);
-    else
-        hipLaunchKernelGGL(sdpa_merge_kernel<16>, dim3(grid), dim3(256), 0, st, out, ws_ml, ws_acc, NQ,
-                           D, n_chunks);
-    return hipGetLastError();
+        return SEGKV_LAUNCH(sdpa_merge_kernel<4>, dim3(grid), dim3(256), st, out, ws_ml, ws_acc, NQ, D,
+                            n_chunks);
+    if (n_chunks <= 8)
+        return SEGKV_LAUNCH(sdpa_merge_kernel<8>, dim3(grid), dim3(256), st, out, ws_ml, ws_acc, NQ, D,
+                            n_chunks);
+    return SEGKV_LAUNCH(sdpa_merge_kernel<16>, dim3(grid), dim3(256), st, out, ws_ml, ws_acc, NQ, D,
+                        n_chunks);
 }
 
 hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const void* src_v,
@@ -549,16 +546,14 @@ hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const v
     unsigned grid = (unsigned)((n_vec + 255) / 256);
     if (grid > 2048u) grid = 2048u;
     if (grid == 0) grid = 1;
-    hipLaunchKernelGGL(append_kv_kernel, dim3(grid), dim3(256), 0, st, (uint4*)dst_k, (uint4*)dst_v,
-                       (const uint4*)src_k, (const uint4*)src_v, n_vec);
-    return hipGetLastError();
+    return SEGKV_LAUNCH(append_kv_kernel, dim3(grid), dim3(256), st, (uint4*)dst_k, (uint4*)dst_v,
+                        (const uint4*)src_k, (const uint4*)src_v, n_vec);
 }
 
 hipError_t launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st)
 {
-    hipLaunchKernelGGL(stream_read_probe_kernel, dim3(kProbeGroups), dim3(256), 0, st,
-                       (const u32x4_t*)src, bytes / 16, (uint32_t*)sink);
-    return hipGetLastError();
+    return SEGKV_LAUNCH(stream_read_probe_kernel, dim3(kProbeGroups), dim3(256), st,
+                        (const u32x4_t*)src, bytes / 16, (uint32_t*)sink);
 }
 
 }  // namespace segkv

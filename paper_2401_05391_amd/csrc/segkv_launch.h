@@ -7,6 +7,38 @@
 
 namespace segkv {
 
+// Launches a kernel and returns the status of THIS launch: the thread's sticky
+// error is cleared first, so that an error some earlier HIP call of the caller
+// left behind is not mistaken for a rejected launch.
+template <typename... KArgs, typename... Args>
+inline hipError_t launch_checked(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
+                                 Args... args)
+{
+    (void)hipGetLastError();
+    kernel<<<grid, block, 0, stream>>>(args...);
+    return hipGetLastError();
+}
+#define SEGKV_LAUNCH(kernel, grid, block, stream, ...) \
+    ::segkv::launch_checked(kernel, grid, block, stream, __VA_ARGS__)
+
+}  // namespace segkv
+
+namespace segkv {
+
+// Planner overrides for tests and A/B measurements, read from the environment
+// ONCE (first use) and again only on segkv_reload_tuning(): see include/segkv.h.
+struct Tuning {
+    int path;            // SEGKV_PATH: 0 planner's choice, 1 "alu", 2 "mfma"
+    int pair_heads;      // SEGKV_PAIR_HEADS: -1 planner's choice, 0, 1
+    int target_groups;   // SEGKV_TARGET_GROUPS: 0 = default
+    int min_pchunk;      // SEGKV_MIN_PCHUNK: 0 = default
+    int mfma_waves;      // SEGKV_MFMA_WAVES: 0 = planner's choice, 4, 8
+    int heads_per_wave;  // SEGKV_HEADS_PER_WAVE: 0 = planner's choice
+    int prefill_regs;    // SEGKV_PREFILL=regs: 1 keeps the register-staged prefill kernel at D = 128
+};
+const Tuning& tuning();
+void reload_tuning();
+
 struct SdpaParams {
     const _Float16* q;
     _Float16* out;
@@ -37,9 +69,6 @@ struct SdpaParams {
     int lineage_stride;           // 32-bit words per request: header + capacity
     int head_pairs;     // 1: every row holds two adjacent heads of D/2 elements (D = 128 kernel, 64-wide heads)
     int resp_in_last;   // 1: no response chunks; the last chunk walks its prompt rows and the whole response
-#ifdef SEGKV_TIMING
-    unsigned long long* timing;   // tuning builds only: per-wave phase timestamps
-#endif
 };
 
 

@@ -78,9 +78,8 @@ __global__ __launch_bounds__(kLineageThreads) void lineage_update_kernel(uint32_
 hipError_t launch_lineage_update(uint32_t* lineage, const int32_t* parent_row, int B, int W, int t,
                                  int stride, hipStream_t st)
 {
-    hipLaunchKernelGGL(lineage_update_kernel, dim3(B), dim3(kLineageThreads), 0, st, lineage,
-                       parent_row, W, t, stride);
-    return hipGetLastError();
+    return SEGKV_LAUNCH(lineage_update_kernel, dim3(B), dim3(kLineageThreads), st, lineage, parent_row,
+                        W, t, stride);
 }
 
 }  // namespace segkv

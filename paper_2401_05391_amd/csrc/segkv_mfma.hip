@@ -29,43 +29,6 @@
 #include "segkv_device.h"
 #include "segkv_mfma_tile.h"
 
-// Optional phase timestamps for kernel tuning (compiled in only with
-// -DSEGKV_TIMING; slot k of work-group g, wave w lands in p.timing).
-#ifdef SEGKV_TIMING
-#define SEGKV_STAMP(k)                                                                   \
-    do {                                                                                 \
-        if (p.timing && (threadIdx.x & 63) == 0)                                         \
-            p.timing[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (k)] = wall_clock64(); \
-    } while (0)
-#define SEGKV_STAMP_FIRST(k)                                                             \
-    do {                                                                                 \
-        if (p.timing && (threadIdx.x & 63) == 0 &&                                       \
-            p.timing[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (k)] == 0)     \
-            p.timing[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (k)] = wall_clock64(); \
-    } while (0)
-#define SEGKV_PHASE_DECL unsigned long long ph_t = __builtin_readcyclecounter(), ph_acc[4] = {0, 0, 0, 0}
-#define SEGKV_PHASE_BEGIN ph_t = __builtin_readcyclecounter()
-#define SEGKV_PHASE(k)                                       \
-    do {                                                     \
-        const unsigned long long now_ = __builtin_readcyclecounter(); \
-        ph_acc[k] += now_ - ph_t;                            \
-        ph_t = now_;                                         \
-    } while (0)
-#define SEGKV_PHASE_DUMP                                                                   \
-    do {                                                                                   \
-        if (p.timing && (threadIdx.x & 63) == 0)                                           \
-            for (int k_ = 0; k_ < 4; ++k_)                                                 \
-                p.timing[(((size_t)1 << 16) * 16 * 8) + ((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 4 + k_] = ph_acc[k_]; \
-    } while (0)
-#else
-#define SEGKV_STAMP(k) do { } while (0)
-#define SEGKV_STAMP_FIRST(k) do { } while (0)
-#define SEGKV_PHASE_DECL do { } while (0)
-#define SEGKV_PHASE_BEGIN do { } while (0)
-#define SEGKV_PHASE(k) do { } while (0)
-#define SEGKV_PHASE_DUMP do { } while (0)
-#endif
-
 namespace segkv {
 
 // Tile geometry of the decode kernel for head dimension D and QT query slots.
@@ -121,7 +84,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: tile indices stay uniform
-    SEGKV_STAMP(0);
     // MFMA lane roles.  32-slot shape: lane = n + 32 h (n: query column / key row /
     // d within a block, h: which 8 of the 16 contraction slots).  16-slot shape:
     // lane = n + 16 h (h = 0..3: which quarter of the contraction slots).
@@ -236,7 +198,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     }
 
     const uint32_t* const ent = s_list.ent;
-    SEGKV_PHASE_DECL;
     // ---- running state: reference max and partial sum per lane, O^T accumulators ----
     float m_ref[NH], l_part[NH];    // l_part: sum of p over this lane's keys of every tile
 #pragma unroll
@@ -274,6 +235,8 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
     //   16-slot shape: 16 (r / 4) + 4 h + (r % 4)
     auto key_row = [&](int r) { return (WIDE ? 8 : 16) * (r >> 2) + 4 * h + (r & 3); };
     auto compute_tile = [&](int mode, int base, int lo) __attribute__((always_inline)) {
+        // the tile was written to LDS by this wave's own lanes in staging layout
+        wave_lds_exchange_point();
         // S^T = K . Q^T
         float s[NH][NSR];
         if constexpr (WIDE) {
@@ -310,7 +273,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
                 }
             }
         }
-        SEGKV_PHASE(1);
         // logits, tile maximum for this lane's query; P = 2^(z - m_ref), fp16 for the
         // PV product -- per head of the row
         _Float16 ph[NH][NSR];
@@ -365,7 +327,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
                 ph[hd][r] = (_Float16)pr;
             }
         }
-        SEGKV_PHASE(2);
         // O^T += V^T . P^T.  The A operand wants, per lane, several keys of one
         // head-dim column; the V tile is row-major [key][d].  ds_read_b64_tr_b16
         // does the transpose on the way out of LDS: a 16-lane group reads 4 rows x
@@ -411,7 +372,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
                 }
             }
         }
-        SEGKV_PHASE(3);
     };
 
     // ---- one tile stream per work-group: prompt tiles first (Section 3.3: loop
@@ -532,39 +492,31 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         store16(p.resp_v + app_dst, app_v);
     }
     __syncthreads();                                   // Q tile and list flag visible
-    SEGKV_STAMP(1);
     if (is_builder && from_lineage) {
         load_response_list_wave(s_list, p.lineage + (size_t)b * p.lineage_stride,
                                 p.lineage_stride - kLineageHeaderWords, p.W, p.T, s0, s1, lane);
         need_tile(0);
-        SEGKV_STAMP(2);
     } else if (is_builder) {
         build_response_list_wave(s_list, p.parent, (g == 0 && qb == 0) ? p.anc_out : nullptr, p.B,
                                  p.W, p.T, b, s0, s1, lrows, lane);
         need_tile(0);                                  // final: this wave has just built it
-        SEGKV_STAMP(2);
     }
     if (!early) {
         if (ti >= n_ptiles) need_tile(ti - n_ptiles);
         fetch(st, ti);
     }
-    SEGKV_PHASE_BEGIN;
     // One turn: the tile has landed -> LDS, the registers are refilled with the
     // wave's next tile, the tile in LDS is multiplied.  (Two tiles in flight per
     // wave measured slower: the CU's outstanding-load limit, not the wave's, binds.)
     while (ti < n_tiles) {
         stage_to_lds(st);
-        SEGKV_STAMP_FIRST(3);
         const int nxt = ti + (ti < t_join ? NW - 1 : NW);
         if (nxt >= n_ptiles) need_tile(nxt - n_ptiles);
         fetch(st, nxt);
-        SEGKV_PHASE(0);
         process(ti);
         ti = nxt;
     }
-    SEGKV_PHASE_DUMP;
 
-    SEGKV_STAMP(4);
     // ---- merge the waves through LDS (each wave reuses its own tile region) ----
 #pragma unroll
     for (int hd = 0; hd < NH; ++hd) {
@@ -590,7 +542,6 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
         }
     }
     __syncthreads();
-    SEGKV_STAMP(5);
 
     const int NQ = N * p.Hq;
     const int nq_here = min(QT, p.nq - qb * QT);
@@ -631,29 +582,23 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             }
         }
     }
-    SEGKV_STAMP(6);
 }
 
 // ---------------------------------------------------------------------------
 // Host-side launcher
 // ---------------------------------------------------------------------------
 template <int D, int NW, int QT>
-static void launch_variant(const SdpaParams& p, unsigned grid, hipStream_t st)
+static hipError_t launch_variant(const SdpaParams& p, unsigned grid, hipStream_t st)
 {
     if constexpr (D == 128 && QT == 16) {
-        if (p.head_pairs) {     // planner: never with several query blocks
-            hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT, false, true>), dim3(grid),
-                               dim3(NW * 64), 0, st, p);
-            return;
-        }
+        if (p.head_pairs)       // planner: never with several query blocks
+            return SEGKV_LAUNCH((sdpa_decode_mfma_kernel<D, NW, QT, false, true>), dim3(grid),
+                                dim3(NW * 64), st, p);
     }
     // several query blocks per unit: the variant whose blocks share K/V rows through L2
     if (p.n_qblocks > 1)
-        hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT, true>), dim3(grid), dim3(NW * 64), 0,
-                           st, p);
-    else
-        hipLaunchKernelGGL((sdpa_decode_mfma_kernel<D, NW, QT, false>), dim3(grid), dim3(NW * 64), 0,
-                           st, p);
+        return SEGKV_LAUNCH((sdpa_decode_mfma_kernel<D, NW, QT, true>), dim3(grid), dim3(NW * 64), st, p);
+    return SEGKV_LAUNCH((sdpa_decode_mfma_kernel<D, NW, QT, false>), dim3(grid), dim3(NW * 64), st, p);
 }
 
 hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, int NW, unsigned grid,
@@ -663,22 +608,18 @@ hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, int NW, u
     if (NW == 4 && (QT != 16 || D > 128)) return hipErrorInvalidValue;
     switch (D) {
         case 64:
-            if (QT == 32)     launch_variant<64, 8, 32>(p, grid, st);
-            else if (NW == 8) launch_variant<64, 8, 16>(p, grid, st);
-            else              launch_variant<64, 4, 16>(p, grid, st);
-            break;
+            if (QT == 32) return launch_variant<64, 8, 32>(p, grid, st);
+            if (NW == 8)  return launch_variant<64, 8, 16>(p, grid, st);
+            return launch_variant<64, 4, 16>(p, grid, st);
         case 128:
-            if (QT == 32)     launch_variant<128, 8, 32>(p, grid, st);
-            else if (NW == 8) launch_variant<128, 8, 16>(p, grid, st);
-            else              launch_variant<128, 4, 16>(p, grid, st);
-            break;
+            if (QT == 32) return launch_variant<128, 8, 32>(p, grid, st);
+            if (NW == 8)  return launch_variant<128, 8, 16>(p, grid, st);
+            return launch_variant<128, 4, 16>(p, grid, st);
         case 256:
             if (QT == 32) return hipErrorInvalidValue;   // accumulators would not fit: planner uses 16
-            launch_variant<256, 8, 16>(p, grid, st);
-            break;
+            return launch_variant<256, 8, 16>(p, grid, st);
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 }  // namespace segkv

@@ -1,6 +1,6 @@
 // libsegkv device code: prefill-phase attention (arxiv 2401.05391, Section 3.1
-// prefill phase and Section 3.3: "a special case of [the decode kernel], only
-// using input tensors of query and prompt key/value").  Batch-first tensors,
+// prefill phase; Section 3.3: prefill is the decode kernel restricted to the
+// query and the prompt key/value).  Batch-first tensors,
 // no transposes: q/out [B, N0, Hq, D], k/v [B, N0, Hkv, D]; k/v ARE the prompt
 // segment that the decode kernel reads afterwards.  Causal: token i sees keys
 // 0..i of its own request.
@@ -226,6 +226,7 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
             *reinterpret_cast<half4_t*>(obuf + n * OROWB + ((32 * db + 8 * i + 4 * h) << 1)) = o4;
         }
     // the wave reads back only what it wrote itself
+    wave_lds_exchange_point();
     constexpr int kRowsPerPass = 64 / CPR;
 #pragma unroll
     for (int r0 = 0; r0 < kQueryTile; r0 += kRowsPerPass) {
@@ -441,6 +442,7 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
             o4.w = (_Float16)(o_acc[db][4 * i + 3] * inv);
             *reinterpret_cast<half4_t*>(obuf + n * OROWB + ((32 * db + 8 * i + 4 * h) << 1)) = o4;
         }
+    wave_lds_exchange_point();                       // the wave reads back only what it wrote itself
     constexpr int kRowsPerPass = 64 / CPR;
 #pragma unroll
     for (int r0 = 0; r0 < kQueryTile; r0 += kRowsPerPass) {
@@ -460,18 +462,15 @@ hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
     const int n_qblocks = (p.N0 + nw * kQueryTile - 1) / (nw * kQueryTile);
     const unsigned grid = (unsigned)((size_t)p.B * p.Hq * n_qblocks);
     const dim3 block(nw * 64);
-    // SEGKV_PREFILL=regs keeps the register-staged kernel at D = 128 (A/B measurements, tests)
-    const char* env = std::getenv("SEGKV_PREFILL");
-    const bool direct = D == 128 && !(env && env[0] == 'r');
+    // the test-only override keeps the register-staged kernel at D = 128
+    const bool direct = D == 128 && !tuning().prefill_regs;
     switch (D) {
-        case 64:  hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, 0, st, p); break;
+        case 64:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, st, p);
         case 128:
-            if (direct) hipLaunchKernelGGL(sdpa_prefill_direct_kernel, dim3(grid), block, 0, st, p);
-            else hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, 0, st, p);
-            break;
-        default:  hipLaunchKernelGGL(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, 0, st, p); break;
+            if (direct) return SEGKV_LAUNCH(sdpa_prefill_direct_kernel, dim3(grid), block, st, p);
+            return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, st, p);
+        default:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, st, p);
     }
-    return hipGetLastError();
 }
 
 }  // namespace segkv

@@ -107,10 +107,8 @@ __global__ __launch_bounds__(kRopeThreads) void rope_append_kernel(RopeParams p)
 hipError_t launch_rope_append(const RopeParams& p, int interleaved, int rows, hipStream_t st)
 {
     if (interleaved)
-        hipLaunchKernelGGL(rope_append_kernel<true>, dim3(rows), dim3(kRopeThreads), 0, st, p);
-    else
-        hipLaunchKernelGGL(rope_append_kernel<false>, dim3(rows), dim3(kRopeThreads), 0, st, p);
-    return hipGetLastError();
+        return SEGKV_LAUNCH(rope_append_kernel<true>, dim3(rows), dim3(kRopeThreads), st, p);
+    return SEGKV_LAUNCH(rope_append_kernel<false>, dim3(rows), dim3(kRopeThreads), st, p);
 }
 
 }  // namespace segkv

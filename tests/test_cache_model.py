@@ -56,6 +56,24 @@ def test_library_matches_the_oracle():
     assert segkv.response_capacity(-3) == 0
 
 
+def test_growth_rule_keeps_exactly_the_valid_rows_hand_case():
+    # Section 3.2: a longer buffer is allocated and the old rows are copied over.  Hand
+    # case, written out: 3 valid rows of a 4-row buffer moved into 6 rows filled with -1.
+    old = np.array([[10, 11], [20, 21], [30, 31], [99, 99]], dtype=np.int32)      # row 3 is not valid
+    got = cache_model.grow(old, 3, 6, -1)
+    want = [[10, 11], [20, 21], [30, 31], [-1, -1], [-1, -1], [-1, -1]]
+    assert got.tolist() == want                       # row T itself is `fill`, not the stale row
+    assert got.dtype == old.dtype and got.shape == (6, 2)
+    assert old.tolist() == [[10, 11], [20, 21], [30, 31], [99, 99]]               # the old buffer is untouched
+    # T = 0 copies nothing; T = capacity copies everything
+    assert cache_model.grow(old, 0, 5, 7).tolist() == [[7, 7]] * 5
+    assert cache_model.grow(old, 4, 5, 7).tolist() == old.tolist() + [[7, 7]]
+    # higher-rank rows keep their shape, and fp16 NaN fill survives
+    k = np.arange(2 * 3 * 2, dtype=np.float16).reshape(2, 3, 2)
+    g = cache_model.grow(k, 1, 3, np.float16(np.nan))
+    assert g.shape == (3, 3, 2) and np.array_equal(g[0], k[0]) and np.isnan(g[1:]).all()
+
+
 def test_segment_never_exceeds_standard_by_more_than_the_growth_slack():
     tok = cache_model.cache_token(40, 40, 128, 2)
     for nres in range(1, 70):

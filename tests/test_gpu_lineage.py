@@ -85,7 +85,7 @@ CASES = [
     (Workload("lin_no_prompt", B=2, W=4, Hq=4, Hkv=4, D=128, Lp=0, T=130, seed=605), {}, True),
     # a response too long for one work-group's list: chunks of the response, each
     # looking up its own range of the list
-    (Workload("lin_response_chunks", B=1, W=4, Hq=4, Hkv=4, D=128, Lp=96, T=1300, seed=606), {}, False),
+    (Workload("lin_response_chunks", B=1, W=4, Hq=4, Hkv=4, D=128, Lp=96, T=1300, seed=606), {}, True),
     (Workload("lin_greedy", B=4, W=1, Hq=8, Hkv=8, D=128, Lp=50, T=20, parents="identity", seed=607), {}, True),
     # two adjacent 64-wide heads per work-group
     (Workload("lin_head_pairs", B=2, W=4, Hq=4, Hkv=4, D=64, Lp=70, T=90, alibi=True, seed=608),
@@ -94,11 +94,11 @@ CASES = [
 
 
 @pytest.mark.parametrize("wl,knobs,with_oracle", CASES, ids=[c[0].name for c in CASES])
-def test_attention_from_the_list_equals_attention_from_the_parent_table(wl, knobs, with_oracle, monkeypatch):
+def test_attention_from_the_list_equals_attention_from_the_parent_table(wl, knobs, with_oracle, planner_env):
     import torch
     import paper_2401_05391_amd as segkv
     for k, v in knobs.items():
-        monkeypatch.setenv(k, str(v))
+        planner_env(**{k: v})
     x = make_inputs(wl)
     dev = torch.device("cuda:0")
     up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
@@ -203,6 +203,13 @@ def test_random_shapes_list_against_parent_table(wl):
     segkv.sdpa_decode_lineage(c, *args, lin, cap, dims, wl.scale, alibi_slopes=up(x["slopes"]), workspace=ws)
     torch.cuda.synchronize()
     _assert_same_attention(c.cpu().numpy(), a.cpu().numpy(), wl.T, wl.name)
+    # and both against the oracle, which resolves the lineage from the parent table
+    ork, orv = x["resp_k"].copy(), x["resp_v"].copy()
+    oracle.append_kv(ork, orv, x["k_new"], x["v_new"], wl.T - 1)
+    ref, _, _ = oracle.sdpa_decode(x["q"], x["prompt_k"], x["prompt_v"], ork, orv, x["parent"], wl.W, wl.T,
+                                   wl.scale, slopes=x["slopes"])
+    assert_parity(c.cpu().numpy(), ref, f"{wl.name}/list")
+    assert_parity(a.cpu().numpy(), ref, f"{wl.name}/parent table")
 
 
 def test_step_by_step_generation_with_the_list():

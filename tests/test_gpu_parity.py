@@ -21,24 +21,6 @@ def _announce(request):
     yield
 
 
-@pytest.fixture
-def planner_env():
-    """Temporarily force the launch planner (chunking) through its documented knobs."""
-    saved = {k: os.environ.get(k) for k in ("SEGKV_TARGET_GROUPS", "SEGKV_MIN_PCHUNK", "SEGKV_PATH",
-                                             "SEGKV_MFMA_WAVES",
-                                            "SEGKV_HEADS_PER_WAVE")}
-
-    def set_env(**kw):
-        for k, v in kw.items():
-            os.environ[k] = str(v)
-    yield set_env
-    for k, v in saved.items():
-        if v is None:
-            os.environ.pop(k, None)
-        else:
-            os.environ[k] = v
-
-
 # Sizes the oracle finishes in well under a second, spanning several key tiles
 # (a tile is 8..32 rows) with ragged tails, every head dim, odd beam widths,
 # grouped queries, ALiBi, no prompt, first step.
@@ -284,16 +266,48 @@ def test_full_size_d64_multi_head_shape_runs_as_head_pairs():
     _check(wl, x, res, ref_out, ref_anc, ref_rk, ref_rv, wl.name)
 
 
-@pytest.mark.parametrize("bs", [1, 4])
+@pytest.mark.parametrize("bs", [1, 4, 8])
 def test_fig6_llama2_13b_shape(bs):
-    # the paper's own kernel experiment (Section 4.1, Figure 6) at two of its batch
-    # sizes: batch 1 exercises the split-KV plan, batch 4 more units than one round
+    # the paper's own kernel experiment (Section 4.1, Figure 6) at three of its batch
+    # sizes: batch 1 exercises the split-KV plan, batch 4 two chunks per unit, batch 8
+    # a unit count between one and two work-groups per CU
     from paper_2401_05391_amd.workloads import fig6_workload
     wl = fig6_workload(bs)
     x = make_inputs(wl)
     res = run_gpu(wl, x, fused=True)
     ref_out, ref_anc, ref_rk, ref_rv = oracle_reference(wl, x)
     _check(wl, x, res, ref_out, ref_anc, ref_rk, ref_rv, wl.name)
+
+
+@pytest.mark.parametrize("bs", [4, 8])
+def test_fig6_shape_with_the_prompt_stored_sequence_first(bs):
+    # the second arm of Section 4.1's layout comparison at the figure's own shape, in
+    # the launch configuration the benchmark times: against the oracle (which is given
+    # the batch-first view of the same values) and against the batch-first call
+    import torch
+    import paper_2401_05391_amd as segkv
+    from paper_2401_05391_amd.workloads import fig6_workload
+    wl = fig6_workload(bs)
+    x = make_inputs(wl)
+    base = run_gpu(wl, x, fused=True)
+    dev = torch.device("cuda:0")
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
+    nbytes = segkv.workspace_bytes(dims)
+    ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=dev) if nbytes else None
+    pk = up(x["prompt_k"]).transpose(0, 1).contiguous()
+    pv = up(x["prompt_v"]).transpose(0, 1).contiguous()
+    assert pk.shape == (wl.Lp, wl.B, wl.Hkv, wl.D)
+    rk, rv = up(x["resp_k"]), up(x["resp_v"])
+    out = torch.full((wl.N, wl.Hq, wl.D), float("nan"), dtype=torch.float16, device=dev)
+    anc = torch.full((wl.T, wl.N), -1, dtype=torch.int32, device=dev)
+    segkv.sdpa_decode_seq_first_prompt(out, up(x["q"]), pk, pv, rk, rv, up(x["parent"]), dims, wl.scale,
+                                       k_new=up(x["k_new"]), v_new=up(x["v_new"]), anc_out=anc, workspace=ws)
+    torch.cuda.synchronize()
+    res = dict(out=out.cpu().numpy(), anc=anc.cpu().numpy(), resp_k=rk.cpu().numpy(), resp_v=rv.cpu().numpy())
+    ref_out, ref_anc, ref_rk, ref_rv = oracle_reference(wl, x)
+    _check(wl, x, res, ref_out, ref_anc, ref_rk, ref_rv, f"{wl.name}/sequence-first prompt")
+    assert same_bits(res["out"], base["out"]), "the two prompt layouts must give the same bits"
 
 
 RAGGED = [
@@ -409,8 +423,8 @@ PAIRED = [
 
 
 @pytest.mark.parametrize("wl,knobs", PAIRED, ids=[c[0].name for c in PAIRED])
-def test_head_pairs_forced(wl, knobs, planner_env, monkeypatch):
-    monkeypatch.setenv("SEGKV_PAIR_HEADS", "1")
+def test_head_pairs_forced(wl, knobs, planner_env):
+    planner_env(SEGKV_PAIR_HEADS=1)
     planner_env(**knobs)
     x = make_inputs(wl)
     ref = oracle_reference(wl, x)
@@ -419,10 +433,10 @@ def test_head_pairs_forced(wl, knobs, planner_env, monkeypatch):
 
 
 @pytest.mark.parametrize("pair", ["0", "auto"])
-def test_head_pairs_at_the_planners_threshold(pair, monkeypatch):
+def test_head_pairs_at_the_planners_threshold(pair, planner_env):
     # 384 (request, head) units: paired by default, one head per work-group when switched off
     if pair != "auto":
-        monkeypatch.setenv("SEGKV_PAIR_HEADS", pair)
+        planner_env(SEGKV_PAIR_HEADS=pair)
     wl = Workload("pair_auto", B=24, W=2, Hq=16, Hkv=16, D=64, Lp=40, T=6, alibi=True, seed=509)
     x = make_inputs(wl)
     ref = oracle_reference(wl, x)
@@ -430,11 +444,11 @@ def test_head_pairs_at_the_planners_threshold(pair, monkeypatch):
     _check(wl, x, res, *ref, what=f"{wl.name}/{pair}")
 
 
-def test_head_pairs_with_per_request_prompt_lengths_in_both_prompt_layouts(monkeypatch):
+def test_head_pairs_with_per_request_prompt_lengths_in_both_prompt_layouts(planner_env):
     import torch
     import paper_2401_05391_amd as segkv
     from oracle import segkv_oracle as oracle
-    monkeypatch.setenv("SEGKV_PAIR_HEADS", "1")
+    planner_env(SEGKV_PAIR_HEADS=1)
     wl = Workload("pair_ragged", B=3, W=4, Hq=4, Hkv=4, D=64, Lp=120, T=40, alibi=True, seed=510)
     lens = np.asarray([120, 5, 77], dtype=np.int32)
     x = make_inputs(wl)

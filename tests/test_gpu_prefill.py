@@ -43,13 +43,13 @@ CASES = [
 
 @pytest.mark.parametrize("staging", ["direct", "regs"])
 @pytest.mark.parametrize("B,N0,Hq,Hkv,D,alibi", CASES)
-def test_prefill_matches_oracle(B, N0, Hq, Hkv, D, alibi, staging, monkeypatch):
+def test_prefill_matches_oracle(B, N0, Hq, Hkv, D, alibi, staging, planner_env):
     # D = 128 has two kernels: tiles copied straight into LDS (the default) and
     # tiles staged through registers (SEGKV_PREFILL=regs); other D ignore the knob
     from oracle import segkv_oracle as oracle
     if staging == "regs" and D != 128:
         pytest.skip("one kernel only at this head dimension")
-    monkeypatch.setenv("SEGKV_PREFILL", staging)
+    planner_env(SEGKV_PREFILL=staging)
     print(f"\n[case] prefill B={B} N0={N0} Hq={Hq} Hkv={Hkv} D={D} alibi={alibi}", flush=True)
     q, k, v = _draw(B, N0, Hq, Hkv, D, 1000 + N0)
     slopes = alibi_slopes(Hq) if alibi else None
@@ -76,20 +76,36 @@ def test_prefill_is_deterministic_and_ignores_future_keys():
     assert np.max(np.abs(a[:, :150].astype(np.float64) - c[:, :150].astype(np.float64))) <= 1e-3
 
 
-def test_llama2_7b_prompt_shape_sampled_rows():
-    # full benchmark shape (one request batch of 4), oracle on sampled rows
+def _bench_prefill_shapes():
+    from bench import PREFILL_SHAPES
+    return PREFILL_SHAPES
+
+
+@pytest.mark.parametrize("name,B,N0,Hq,Hkv,D", _bench_prefill_shapes(), ids=[c[0] for c in _bench_prefill_shapes()])
+def test_benchmark_prompt_shapes_sampled_rows(name, B, N0, Hq, Hkv, D):
+    # every shape `bench.py --prefill` quotes, at the batch size it times; the oracle
+    # computes sampled (request, token, head) rows one by one: tile and query-block
+    # boundaries, the first and the last token, every query head of one KV group
+    # (grouped-query shapes), and random rows
     from oracle import segkv_oracle as oracle
-    B, N0, Hq, Hkv, D = 4, 1024, 32, 32, 128
-    print("\n[case] prefill llama2-7b shape", flush=True)
+    print(f"\n[case] prefill {name} B={B} N0={N0} Hq={Hq} Hkv={Hkv} D={D}", flush=True)
     q, k, v = _draw(B, N0, Hq, Hkv, D, 99)
     scale = 1.0 / np.sqrt(D)
     got = _run(q, k, v, scale)
+    print("[gpu done]", flush=True)
     rng = np.random.default_rng(5)
-    rows = np.stack([rng.integers(0, B, 600), rng.integers(0, N0, 600), rng.integers(0, Hq, 600)], 1)
-    rows[:8, 1] = [0, 1, 31, 32, 127, 128, 1022, 1023]
-    ref = oracle.sdpa_prefill(q, k, v, scale, rows=rows.astype(np.int32))
+    edges = sorted({t for t in (0, 1, 15, 16, 31, 32, 33, 127, 128, 255, 256, 257, N0 // 2 - 1, N0 // 2,
+                                N0 - 129, N0 - 128, N0 - 33, N0 - 32, N0 - 2, N0 - 1) if 0 <= t < N0})
+    G = Hq // Hkv
+    fixed = [(b, t, h) for b in (0, B - 1) for t in edges for h in (0, Hq - 1)]
+    fixed += [(B // 2, t, (Hkv // 2) * G + j) for t in (edges[3], edges[-1], N0 // 3) for j in range(G)]
+    rnd = np.stack([rng.integers(0, B, 400), rng.integers(0, N0, 400), rng.integers(0, Hq, 400)], 1)
+    rows = np.concatenate([np.asarray(fixed, dtype=np.int64), rnd]).astype(np.int32)
+    ref = oracle.sdpa_prefill(q, k, v, scale, rows=rows)
     sel = got[rows[:, 0], rows[:, 1], rows[:, 2]]
-    assert_parity(sel, ref, "prefill 7b sampled")
+    max_abs, rel_l2 = assert_parity(sel, ref, f"prefill {name} sampled")
+    print(f"[parity] {name}: {len(rows)} rows, max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}", flush=True)
+    assert np.all(np.isfinite(got.astype(np.float32))), "non-finite output outside the sampled rows"
 
 
 def test_prefill_then_first_decode_step_share_the_prompt_segment():

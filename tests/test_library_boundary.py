@@ -69,8 +69,8 @@ def test_decode_rejects_bad_arguments_without_a_device():
         assert _decode(segkv.make_dims(**{**good, **bad})) == binding.SEGKV_UNSUPPORTED
 
 
-def test_workspace_requirement_is_enforced(monkeypatch):
-    monkeypatch.setenv("SEGKV_TARGET_GROUPS", str(1 << 20))    # force split-KV
+def test_workspace_requirement_is_enforced(planner_env):
+    planner_env(SEGKV_TARGET_GROUPS=1 << 20)    # force split-KV
     d = segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=512, T=5, Tcap=16)
     need = segkv.workspace_bytes(d)
     assert need > 0 and need % 16 == 0
@@ -97,6 +97,26 @@ def test_static_scratch_entry_point_rejects_oversized_dimensions_without_a_devic
     assert call(ok, out=None) == binding.SEGKV_INVALID_ARG
     assert call(segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=96, Lp=64, T=5, Tcap=16)) == binding.SEGKV_UNSUPPORTED
     assert call(segkv.make_dims(B=2, beam=4, Hq=8, Hkv=2, D=128, Lp=64, T=0, Tcap=16)) == binding.SEGKV_INVALID_ARG
+
+
+def test_planner_overrides_are_read_once_and_again_only_on_reload(planner_env):
+    # a stray environment variable set after the first call must not change which plan ships
+    d = segkv.make_dims(B=64, beam=1, Hq=8, Hkv=8, D=128, Lp=512, T=5, Tcap=16)
+    before = segkv.workspace_bytes(d)
+    assert before == 0                                        # 512 units: one work-group per unit
+    os.environ["SEGKV_TARGET_GROUPS"] = str(1 << 20)
+    try:
+        assert segkv.workspace_bytes(d) == before            # not re-read
+        planner_env(SEGKV_TARGET_GROUPS=1 << 20)              # sets and reloads
+        assert segkv.workspace_bytes(d) > before
+    finally:
+        os.environ.pop("SEGKV_TARGET_GROUPS", None)
+
+
+def test_hip_error_status_carries_the_runtime_text():
+    text = segkv.status_string(binding.SEGKV_HIP_ERROR)
+    assert text.startswith("HIP runtime rejected a kernel launch: ")
+    assert len(text) > len("HIP runtime rejected a kernel launch: ")
 
 
 def test_append_rejects_bad_arguments_without_a_device():
