@@ -541,7 +541,7 @@ def main():
 
     import torch
     import paper_2401_05391_amd as segkv
-    from paper_2401_05391_amd.workloads import CONFIGS
+    from paper_2401_05391_amd.workloads import RESPONSE_HEAVY, find_workload
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -570,16 +570,24 @@ def main():
             "roofline": last["roofline"], "sweep": rows}), flush=True)
         return
 
-    wl = CONFIGS[a.workload]
+    wl = find_workload(a.workload)
     main_res = time_workload(wl, a.steps, a.warmup, segkv, torch, not a.no_cpu_baseline, a.cpu_seconds,
                              use_lineage=a.lineage)
     others = []
     for name in [n for n in a.others.split(",") if n and n != a.workload]:
-        others.append(time_workload(CONFIGS[name], a.steps, a.warmup, segkv, torch, False, 0,
+        others.append(time_workload(find_workload(name), a.steps, a.warmup, segkv, torch, False, 0,
                                     use_lineage=a.lineage))
 
     # the rows next to the path: the paper's Figure 6 sweep (both prompt layouts) and the
     # prefill attention, each timed the same way, each with its own roofline
+    resp_heavy = None
+    if not a.no_extras:
+        resp_heavy = []
+        for w in RESPONSE_HEAVY.values():
+            r = time_workload(w, max(a.steps // 2, 10), a.warmup, segkv, torch, False, 0, probe=False)
+            resp_heavy.append({k: r[k] for k in ("workload", "shape", "timed_launches", "us_per_layer_step",
+                                                 "gbs_unique", "gbs_nominal", "bytes_unique",
+                                                 "unique_response_rows", "roofline", "buffer_sets")})
     fig6 = None if a.no_extras else fig6_rows(a.steps, a.warmup, segkv, torch)
     prefill = None if a.no_extras else prefill_rows(max(a.steps // 4, 10), a.warmup, segkv, torch)
 
@@ -612,6 +620,10 @@ def main():
                                                "per_launch_event_pairs_us", "roofline",
                                                "stream_read_probe_gbs", "buffer_sets")}
                             for r in others],
+        "response_heavy": None if resp_heavy is None else {
+            "what": "Section 3.2's sizes (N_prompt = N_response = 1024, beam 4, batch 32) on the GPT-J-6B and "
+                    "Llama2-13B attention shapes: the response segment as long as the prompt",
+            "workloads": resp_heavy},
         "fig6": None if fig6 is None else {
             "what": "Section 4.1, Figure 6: Llama2-13B attention shape (40 heads of 128), beam 4, 1024 "
                     "prompt / 128 response tokens; prompt segment batch first and sequence first",

@@ -77,6 +77,29 @@ def fig6_workload(batch_size: int) -> Workload:
                     Lp=1024, T=128, seed=13)
 
 
+# Section 3.2 sizes its memory example at N_prompt = N_response = 1024, beam
+# width 4, batch 32: the point where the response segment is as long as the
+# prompt.  Same two model shapes as Section 4's single-tile models.
+RESPONSE_HEAVY: Dict[str, Workload] = {
+    "gptj6b_1024_1024": Workload("gptj6b_1024_1024", B=32, W=4, Hq=16, Hkv=16, D=256,
+                                 Lp=1024, T=1024, seed=21),
+    "llama2_13b_1024_1024": Workload("llama2_13b_1024_1024", B=32, W=4, Hq=40, Hkv=40, D=128,
+                                     Lp=1024, T=1024, seed=22),
+}
+
+
+def find_workload(name: str) -> Workload:
+    """A workload by name: the benchmark configurations, the response-heavy
+    points, or llama2_13b_bs<N> of the Figure 6 sweep."""
+    if name in CONFIGS:
+        return CONFIGS[name]
+    if name in RESPONSE_HEAVY:
+        return RESPONSE_HEAVY[name]
+    if name.startswith("llama2_13b_bs"):
+        return fig6_workload(int(name[len("llama2_13b_bs"):]))
+    raise KeyError(name)
+
+
 def alibi_slopes(Hq: int) -> np.ndarray:
     """Per-head slopes 2^(-8 h / Hq), h = 1..Hq (fp32).  The formula lives only
     here; both the oracle and the GPU library take the array as an input."""

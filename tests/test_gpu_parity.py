@@ -254,6 +254,27 @@ def test_full_size_configs(name):
     assert same_bits(res["resp_v"][wl.T - 1], x["v_new"])
 
 
+@pytest.mark.parametrize("name", ["gptj6b_1024_1024", "llama2_13b_1024_1024"])
+def test_response_as_long_as_the_prompt_full_size(name):
+    # Section 3.2's sizes (1024 prompt tokens, 1024 response steps, beam 4, batch 32):
+    # 4096 (step, beam) rows per request in one work-group's list, several windows
+    # of the lineage scan; every output row against the oracle
+    from paper_2401_05391_amd.workloads import RESPONSE_HEAVY
+    wl = RESPONSE_HEAVY[name]
+    x = make_inputs(wl)
+    print(f"[inputs drawn] {name}", flush=True)
+    res = run_gpu(wl, x, fused=True)
+    print(f"[gpu done] {name}", flush=True)
+    ref_out, ref_anc, ref_rk, ref_rv = oracle_reference(wl, x)
+    print(f"[oracle done] {name}", flush=True)
+    assert np.array_equal(res["anc"], ref_anc)
+    max_abs, rel_l2 = assert_parity(res["out"], ref_out, name)
+    print(f"[parity] {name}: max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}", flush=True)
+    assert same_bits(res["resp_k"][wl.T - 1], x["k_new"])
+    assert same_bits(res["resp_v"][wl.T - 1], x["v_new"])
+    assert same_bits(res["resp_k"][: wl.T - 1], x["resp_k"][: wl.T - 1])
+
+
 def test_full_size_d64_multi_head_shape_runs_as_head_pairs():
     # 1024 (request, head) units of 64-element heads: the planner pairs adjacent heads
     import paper_2401_05391_amd as segkv
