@@ -293,6 +293,9 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     const int wq0 = q0 + wave * kQueryTile;
     const int qi = wq0 + n;
     const float slope2 = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
+    // the scale enters as |scale| (its sign is moved into Q), so that the maximum of
+    // the raw products of a tile is the maximum of its scaled logits
+    const float scale2 = fabsf(p.scale2);
 
     // ---- tile copies: this wave's share is INS_PER_WAVE instructions per operand ----
     const int k_end = min(q0 + kQueries, p.N0);
@@ -326,9 +329,13 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     {
         const int qrow = min(qi, p.N0 - 1);
         const _Float16* qp = p.q + (((size_t)b * p.N0 + qrow) * p.Hq + hq) * D;
+        const uint32_t flip = p.scale2 < 0.0f ? 0x80008000u : 0u;
 #pragma unroll
-        for (int t = 0; t < NKS; ++t)
-            qreg[t] = __builtin_bit_cast(half8_t, load16(qp + 16 * t + 8 * h));
+        for (int t = 0; t < NKS; ++t) {
+            u32x4_t w = load16(qp + 16 * t + 8 * h);
+            w.x ^= flip; w.y ^= flip; w.z ^= flip; w.w ^= flip;
+            qreg[t] = __builtin_bit_cast(half8_t, w);
+        }
         // The compiler's wait for these loads must sit here and not inside the tile
         // loop, where it would also wait for the tile copies in flight (which it
         // does not know of).
@@ -362,18 +369,20 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
                 *reinterpret_cast<const half8_t*>(k_tile + n * ROWB + (((2 * t + h) << 4) ^ kx));
             s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
         }
+        // plain tiles keep the raw products in s and apply the scale inside the
+        // exponent's multiply-add; masked tiles finish their logits here
+        const bool plain = !diagonal && p.slopes == nullptr;
+        const float mult = plain ? scale2 : 1.0f;
         float m_tile = -INFINITY;
-        if (!diagonal && p.slopes == nullptr) {
+        if (plain) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s[r] *= p.scale2;
-                m_tile = fmaxf(m_tile, s[r]);
-            }
+            for (int r = 0; r < 16; ++r) m_tile = fmaxf(m_tile, s[r]);
+            m_tile *= scale2;
         } else {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = base + 8 * (r >> 2) + 4 * h + (r & 3);
-                const float z = s[r] * p.scale2 + slope2 * (float)(key - qi);
+                const float z = s[r] * scale2 + slope2 * (float)(key - qi);
                 s[r] = (key <= qi) ? z : -INFINITY;
                 m_tile = fmaxf(m_tile, s[r]);
             }
@@ -392,7 +401,7 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         half8_t pb[2];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float pr = fast_exp2(s[r] - m_ref);
+            const float pr = fast_exp2(__builtin_fmaf(s[r], mult, -m_ref));
             l_part += pr;
             pb[r >> 3][r & 7] = (_Float16)pr;
         }
