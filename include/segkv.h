@@ -293,7 +293,7 @@ const char* segkv_status_string(int status);
  * variables so that tests and A/B measurements reach every kernel and plan on
  * small inputs: SEGKV_PATH (alu | mfma), SEGKV_TARGET_GROUPS, SEGKV_MIN_PCHUNK,
  * SEGKV_MFMA_WAVES (4 | 8), SEGKV_HEADS_PER_WAVE (1 | 2 | 4), SEGKV_PAIR_HEADS
- * (0 | 1), SEGKV_PREFILL (regs).  They are read ONCE, on the library's first
+ * (0 | 1), SEGKV_XCD_HEAD_ORDER (0), SEGKV_PREFILL (regs).  They are read ONCE, on the library's first
  * use in the process, so that the workspace size a caller asked for and the
  * launch that follows always agree; this call reads them again.  Not for use
  * while other threads are inside the library.  Results never depend on the

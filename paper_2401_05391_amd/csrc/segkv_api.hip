@@ -67,6 +67,8 @@ segkv::Tuning read_tuning_from_environment()
     t.min_pchunk = env_int("SEGKV_MIN_PCHUNK");
     t.mfma_waves = env_int("SEGKV_MFMA_WAVES");
     t.heads_per_wave = env_int("SEGKV_HEADS_PER_WAVE");
+    const char* xho = std::getenv("SEGKV_XCD_HEAD_ORDER");
+    t.xcd_head_order = (xho && xho[0] == '0') ? 0 : 1;
     const char* prefill = std::getenv("SEGKV_PREFILL");
     t.prefill_regs = (prefill && prefill[0] == 'r') ? 1 : 0;
     return t;
@@ -258,6 +260,45 @@ Plan make_plan(const segkv_dims* d_in)
 
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+// XCD-aware placement of KV heads for the matrix-core kernel.  Work-group i runs
+// on XCD i % 8 and consecutive work-groups take consecutive KV heads, so with a
+// multiple of eight heads every XCD streams the same heads (mod 8) of every
+// request, i.e. fixed 256-byte columns of the K/V rows.  Two things are uneven on
+// MI355X, both measured with per-work-group time stamps on the Llama2-70B shape
+// (256 work-groups, one per CU): the columns whose address bits 9:8 are 01 are
+// served more slowly (a head that streams one finishes 3-4 us later than one
+// that streams none), and the odd-numbered XCDs get a smaller share of the HBM
+// bandwidth than the even ones (about 2 us between their means).  The kernel
+// ends with its slowest work-group, so the heads with slow columns go to the
+// even XCDs.  Returns nibble j = head (mod 8) for position j of every aligned
+// run of eight heads; the identity when nothing is known to be uneven.
+uint32_t xcd_aware_head_order(const void* k_base, const void* v_base, int head_bytes)
+{
+    constexpr uint32_t kIdentity = 0x76543210u;
+    if (!k_base || !v_base || head_bytes < 128 || head_bytes > 1024) return kIdentity;
+    int score[8];
+    for (int j = 0; j < 8; ++j) {
+        score[j] = 0;
+        for (int off = 0; off < head_bytes; off += 128) {
+            const uintptr_t ak = (uintptr_t)k_base + (uintptr_t)j * head_bytes + off;
+            const uintptr_t av = (uintptr_t)v_base + (uintptr_t)j * head_bytes + off;
+            score[j] += (((ak >> 8) & 3u) == 1u) + (((av >> 8) & 3u) == 1u);
+        }
+    }
+    int heads[8] = {0, 1, 2, 3, 4, 5, 6, 7};
+    // stable insertion sort, slowest first
+    for (int i = 1; i < 8; ++i)
+        for (int k = i; k > 0 && score[heads[k]] > score[heads[k - 1]]; --k) {
+            const int t = heads[k];
+            heads[k] = heads[k - 1];
+            heads[k - 1] = t;
+        }
+    static const int kXcdFastFirst[8] = {0, 2, 4, 6, 1, 3, 5, 7};
+    uint32_t perm = 0;
+    for (int k = 0; k < 8; ++k) perm |= (uint32_t)heads[k] << (4 * kXcdFastFirst[k]);
+    return perm;
+}
+
 // A lineage list of `capacity` entries per request can hold `steps` steps of this beam width.
 bool lineage_ok(int32_t capacity, int32_t steps, const segkv_dims* d)
 {
@@ -421,6 +462,10 @@ int sdpa_decode_impl(void* out, const void* q, const void* prompt_k, const void*
     p.rchunk = pl.rchunk;
     p.n_rchunks = pl.n_rchunks;
     p.resp_in_last = pl.resp_in_last;
+    p.head_perm8 = 0x76543210u;
+    if (pl.mfma && pl.Hkv % 8 == 0 && segkv::tuning().xcd_head_order)
+        p.head_perm8 = d->Lp > 0 ? xcd_aware_head_order(prompt_k, prompt_v, pl.D * 2)
+                                 : xcd_aware_head_order(resp_k, resp_v, pl.D * 2);
 
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = pl.mfma ? segkv::launch_sdpa_decode_mfma(p, pl.D, pl.QB, pl.NW, pl.grid, st)

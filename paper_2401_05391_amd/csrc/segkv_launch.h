@@ -34,6 +34,7 @@ struct Tuning {
     int min_pchunk;      // SEGKV_MIN_PCHUNK: 0 = default
     int mfma_waves;      // SEGKV_MFMA_WAVES: 0 = planner's choice, 4, 8
     int heads_per_wave;  // SEGKV_HEADS_PER_WAVE: 0 = planner's choice
+    int xcd_head_order;  // SEGKV_XCD_HEAD_ORDER: 0 keeps consecutive heads on consecutive XCDs, default on
     int prefill_regs;    // SEGKV_PREFILL=regs: 1 keeps the register-staged prefill kernel at D = 128
 };
 const Tuning& tuning();
@@ -68,6 +69,7 @@ struct SdpaParams {
     const uint32_t* lineage;      // null, or the per-request lineage lists (see segkv_lineage.hip)
     int lineage_stride;           // 32-bit words per request: header + capacity
     int head_pairs;     // 1: every row holds two adjacent heads of D/2 elements (D = 128 kernel, 64-wide heads)
+    uint32_t head_perm8;  // matrix-core kernel: nibble j = KV head (mod 8) that position j of a run of eight takes
     int resp_in_last;   // 1: no response chunks; the last chunk walks its prompt rows and the whole response
 };
 

@@ -116,7 +116,12 @@ void sdpa_decode_mfma_kernel(SdpaParams p)
             id = (n_units / 8) * 8 + r / nqb;
         }
     }
-    const int g = id % p.Hkv;        id /= p.Hkv;
+    // Which KV head: consecutive indices are consecutive heads, and within every
+    // aligned run of eight (one per XCD) the planner may permute them so that the
+    // heads whose K/V columns are served more slowly run on the faster XCDs
+    // (identity when it has no reason to).
+    const int g0 = id % p.Hkv;       id /= p.Hkv;
+    const int g = (g0 & ~7) | (int)((p.head_perm8 >> (4 * (g0 & 7))) & 7u);
     const int chunk = id % p.n_chunks;
     const int b = id / p.n_chunks;
     const int N = p.B * p.W;

@@ -18,7 +18,7 @@ def golden_dir():
 
 
 TUNING_KEYS = ("SEGKV_TARGET_GROUPS", "SEGKV_MIN_PCHUNK", "SEGKV_PATH", "SEGKV_MFMA_WAVES",
-               "SEGKV_HEADS_PER_WAVE", "SEGKV_PAIR_HEADS", "SEGKV_PREFILL")
+               "SEGKV_HEADS_PER_WAVE", "SEGKV_PAIR_HEADS", "SEGKV_PREFILL", "SEGKV_XCD_HEAD_ORDER")
 
 
 @pytest.fixture
