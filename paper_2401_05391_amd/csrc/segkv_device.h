@@ -472,13 +472,19 @@ __device__ void load_response_list_wave(WaveListSmem<CAP>& sm, const uint32_t* h
     __hip_atomic_store(&sm.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-// Any other wave: blocks until ent[want .. CAP) is written or the list is final,
-// whichever comes first (the builder never waits for anything, so this ends).
-// Returns the published top and sets `final`.
+// Any other wave: waits until ent[want .. CAP) is written or the list is final,
+// whichever comes first.  Returns the published top and sets `final`.
+// The builder wave never waits for anything (it neither takes a barrier nor
+// reads what other waves produce before it publishes), so the wait ends after
+// one window's worth of composition at most.  The poll is bounded all the same:
+// should a later change break that invariant, the wave leaves after
+// kListWaitPolls polls with an EMPTY list (wrong attention output, which the
+// parity tests catch) instead of occupying the GPU for good.
+constexpr int kListWaitPolls = 1 << 22;   // x ~0.1 us per poll: far beyond any list build
 template <int CAP>
 __device__ __forceinline__ int wait_response_list(WaveListSmem<CAP>& sm, int want, bool& final)
 {
-    for (;;) {
+    for (int poll = 0; poll < kListWaitPolls; ++poll) {
         const int rdy = __builtin_amdgcn_readfirstlane(
             __hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
         const int top = __builtin_amdgcn_readfirstlane(
@@ -489,6 +495,8 @@ __device__ __forceinline__ int wait_response_list(WaveListSmem<CAP>& sm, int wan
         }
         __builtin_amdgcn_s_sleep(2);
     }
+    final = true;
+    return CAP;
 }
 
 }  // namespace segkv

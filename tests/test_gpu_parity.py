@@ -178,6 +178,33 @@ def test_run_twice_is_bit_identical(path, planner_env):
     assert same_bits(res["outs"][0], res["outs"][2])
 
 
+XCD_ORDER_CASES = [
+    # multiples of eight KV heads: the planner may permute which head runs on which XCD
+    Workload("xcd8_w4", B=3, W=4, Hq=8, Hkv=8, D=128, Lp=150, T=37, seed=701),
+    Workload("xcd16_gqa_alibi", B=2, W=2, Hq=32, Hkv=16, D=64, Lp=90, T=21, alibi=True, seed=702),
+    Workload("xcd8_d256", B=2, W=4, Hq=8, Hkv=8, D=256, Lp=70, T=18, seed=703),
+    Workload("xcd24_greedy", B=2, W=1, Hq=24, Hkv=24, D=128, Lp=200, T=40, parents="identity", seed=704),
+]
+
+
+@pytest.mark.parametrize("chunked", [False, True], ids=["default_plan", "chunked"])
+@pytest.mark.parametrize("wl", XCD_ORDER_CASES, ids=lambda w: w.name)
+def test_head_placement_on_xcds_changes_no_bit(wl, chunked, planner_env):
+    # which XCD a (request, head) unit runs on is scheduling only: with the placement
+    # switched off the outputs, the appended rows and the ancestor table are the same bits;
+    # and both agree with the oracle
+    x = make_inputs(wl)
+    knobs = dict(SEGKV_TARGET_GROUPS=1 << 20, SEGKV_MIN_PCHUNK=32) if chunked else {}
+    planner_env(SEGKV_PATH="mfma", SEGKV_XCD_HEAD_ORDER=1, **knobs)
+    placed = run_gpu(wl, x, fused=True)
+    planner_env(SEGKV_XCD_HEAD_ORDER=0)
+    plain = run_gpu(wl, x, fused=True)
+    assert same_bits(placed["out"], plain["out"])
+    assert same_bits(placed["resp_k"], plain["resp_k"]) and same_bits(placed["resp_v"], plain["resp_v"])
+    assert np.array_equal(placed["anc"], plain["anc"])
+    _check(wl, x, placed, *oracle_reference(wl, x), what=f"{wl.name}/placed")
+
+
 @pytest.mark.parametrize("path", ["alu", "mfma"])
 def test_dead_slots_and_rows_beyond_T_are_never_read(path, planner_env):
     planner_env(SEGKV_PATH=path)
