@@ -55,3 +55,52 @@ def test_static_scratch_equals_caller_workspace_twice_in_a_row():
     _run_both(Workload("noalloc_a", B=2, W=4, Hq=8, Hkv=8, D=128, Lp=1500, T=40, seed=901))
     print("[case] static scratch: second call, 4 units of 700 + 12 keys, ALiBi, grouped heads", flush=True)
     _run_both(Workload("noalloc_b", B=1, W=3, Hq=8, Hkv=4, D=64, Lp=700, T=12, alibi=True, seed=902))
+
+
+def test_static_scratch_call_replays_from_a_graph():
+    # the callers this entry point is for: a decode step recorded into a HIP graph (no
+    # allocation possible inside the capture).  The buffer's address is looked up by one
+    # eager call first; the recorded step is replayed with new inputs, eager launches and
+    # synchronisations in between, and every replay must give the bits of the eager
+    # segkv_sdpa_decode call with a caller workspace.
+    import torch
+    import paper_2401_05391_amd as segkv
+
+    dev = torch.device("cuda:0")
+    B, W, Hq, Hkv, D, Lp, T = 1, 4, 8, 8, 128, 600, 11
+    N = B * W
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    rnd = lambda *s: torch.randn(*s, generator=gen, device=dev, dtype=torch.float32).half()
+    tcap = segkv.response_capacity(T)
+    dims = segkv.make_dims(B, W, Hq, Hkv, D, Lp, T, tcap)
+    need = segkv.workspace_bytes(dims)
+    assert 0 < need <= segkv.binding.STATIC_SCRATCH_BYTES
+    pk, pv = rnd(B, Lp, Hkv, D), rnd(B, Lp, Hkv, D)
+    rk, rv = rnd(tcap, N, Hkv, D), rnd(tcap, N, Hkv, D)
+    parent = torch.randint(0, W, (T, N), generator=gen, device=dev, dtype=torch.int32)
+    q = torch.empty(N, Hq, D, dtype=torch.float16, device=dev)
+    out_g = torch.full((N, Hq, D), float("nan"), dtype=torch.float16, device=dev)
+    out_e = torch.full((N, Hq, D), float("nan"), dtype=torch.float16, device=dev)
+    ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device=dev)
+    scale = D ** -0.5
+
+    q.copy_(rnd(N, Hq, D))
+    print("\n[case] static scratch: eager call that looks the buffer up", flush=True)
+    segkv.sdpa_decode_static_scratch(out_g, q, pk, pv, rk, rv, parent, dims, scale)
+    torch.cuda.synchronize()
+    print("[case] static scratch: capture", flush=True)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        segkv.sdpa_decode_static_scratch(out_g, q, pk, pv, rk, rv, parent, dims, scale)
+    torch.cuda.synchronize()
+    for i in range(4):
+        print(f"[case] static scratch: replay {i}", flush=True)
+        q.copy_(rnd(N, Hq, D))
+        segkv.sdpa_decode(out_e, q, pk, pv, rk, rv, parent, dims, scale, workspace=ws)
+        torch.cuda.synchronize()
+        out_g.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert same_bits(out_g.cpu().numpy(), out_e.cpu().numpy()), f"replay {i}"
+        assert not np.isnan(out_g.float().cpu().numpy()).any()
