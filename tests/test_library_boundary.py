@@ -183,3 +183,36 @@ def test_sequence_first_prompt_entry_point_validates_like_the_batch_first_one():
     assert call(bad) == binding.SEGKV_UNSUPPORTED
     wide = segkv.make_dims(B=1 << 20, beam=1, Hq=64, Hkv=64, D=128, Lp=1, T=1, Tcap=1)
     assert call(wide) == binding.SEGKV_UNSUPPORTED           # B*Hkv*D beyond the 32-bit tile offsets
+
+
+def test_workspace_size_and_static_scratch_limit_agree_over_random_dimensions():
+    # host logic only: the size query is deterministic, 16-byte granular, zero exactly when one
+    # work-group covers a unit, and the entry point with the static buffer rejects exactly the
+    # dimensions whose need exceeds its limit (checked before any device call: no GPU here)
+    import random
+    lib = segkv.load_library()
+    rng = random.Random(20240105)
+    call = lambda d_: lib.segkv_sdpa_decode_static_scratch(
+        FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, None, 0.125, ctypes.byref(d_), None)
+    seen_zero = seen_pos = seen_big = 0
+    for _ in range(400):
+        D = rng.choice([64, 128, 256])
+        beam = rng.choice([1, 2, 3, 4, 8])
+        Hkv = rng.choice([1, 2, 4, 8, 16, 40])
+        G = rng.choice([1, 1, 2, 8])
+        B = rng.choice([1, 2, 7, 32, 64, 200])
+        Lp = rng.choice([0, 1, 100, 1024, 5000])
+        T = rng.choice([1, 2, 17, 128, 257, 900, 1500])
+        d = segkv.make_dims(B=B, beam=beam, Hq=Hkv * G, Hkv=Hkv, D=D, Lp=Lp, T=T, Tcap=-(-T // 16) * 16)
+        need = segkv.workspace_bytes(d)
+        assert need == segkv.workspace_bytes(d) and need % 16 == 0
+        if need == 0:
+            seen_zero += 1
+        elif need > binding.STATIC_SCRATCH_BYTES:
+            seen_big += 1
+            assert call(d) == binding.SEGKV_STATIC_SCRATCH_EXCEEDED
+        else:
+            seen_pos += 1
+            # partials are fp32: (m, l) pairs and D accumulators per query and chunk, at least two chunks
+            assert need >= 2 * B * beam * Hkv * G * (D + 2) * 4
+    assert seen_zero and seen_pos and seen_big
