@@ -15,7 +15,7 @@ that 50 us kernels are not timed over a millisecond); `value`, `ms_per_step`
 and `roofline.achieved` all come from it.  The host's wall clock over the same
 region and a per-launch event-pair spread are reported beside it.
 
-Prints ONE JSON line (see README / DESIGN for the fields); besides the headline
+Prints ONE JSON line; besides the headline
 workload it carries the other benchmark configurations, the paper's Figure 6
 batch-size sweep in both prompt layouts, and the prefill attention shapes.
 """
