@@ -184,6 +184,10 @@ XCD_ORDER_CASES = [
     Workload("xcd16_gqa_alibi", B=2, W=2, Hq=32, Hkv=16, D=64, Lp=90, T=21, alibi=True, seed=702),
     Workload("xcd8_d256", B=2, W=4, Hq=8, Hkv=8, D=256, Lp=70, T=18, seed=703),
     Workload("xcd24_greedy", B=2, W=1, Hq=24, Hkv=24, D=128, Lp=200, T=40, parents="identity", seed=704),
+    # 40 queries per KV head: two query blocks per unit, whose work-groups sit 8 indices apart
+    Workload("xcd8_two_query_blocks", B=3, W=8, Hq=40, Hkv=8, D=128, Lp=90, T=25, seed=705),
+    # 64-wide heads run as pairs: 16 heads become 8 rows of two
+    Workload("xcd16_head_pairs", B=30, W=2, Hq=16, Hkv=16, D=64, Lp=60, T=12, alibi=True, seed=706),
 ]
 
 
