@@ -75,26 +75,28 @@ class DeviceSet:
             return torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).half()
 
         self.dims = segkv.make_dims(wl.B, wl.W, wl.Hq, wl.Hkv, wl.D, wl.Lp, wl.T, wl.Tcap)
-        # V buffers are placed at the library's recommended byte offset from a
-        # 1 KB boundary (K buffers sit on one): see segkv_value_stagger_bytes
+        # K buffers sit on an 8 KB boundary, V buffers at the library's recommended byte
+        # offset from one: see segkv_value_stagger_bytes
         stagger = segkv.value_stagger_bytes(self.dims)
 
-        def staggered(t):
-            if not stagger:
-                return t
-            big = torch.empty(t.numel() + 512, dtype=torch.float16, device=dev)
-            assert big.data_ptr() % 1024 == 0
-            v = big[stagger // 2: stagger // 2 + t.numel()].view_as(t)
+        def placed(t, offset):
+            big = torch.empty(t.numel() + 8192, dtype=torch.float16, device=dev)
+            start = (-big.data_ptr()) % 8192 + offset
+            v = big[start // 2: start // 2 + t.numel()].view_as(t)
+            assert (v.data_ptr() - offset) % 8192 == 0
             v.copy_(t)
             return v
+
+        def staggered(t):
+            return placed(t, stagger)
 
         self.q = rnd(wl.N, wl.Hq, wl.D)
         # Section 4.1's layout comparison: [Lp, B, Hkv, D] when prompt_seq_first
         pshape = (wl.Lp, wl.B, wl.Hkv, wl.D) if prompt_seq_first else (wl.B, wl.Lp, wl.Hkv, wl.D)
         self.prompt_seq_first = prompt_seq_first
-        self.pk = rnd(*pshape)
+        self.pk = placed(rnd(*pshape), 0)
         self.pv = staggered(rnd(*pshape))
-        self.rk = torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16, device=dev)
+        self.rk = placed(torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16, device=dev), 0)
         self.rv = staggered(torch.full((wl.Tcap, wl.N, wl.Hkv, wl.D), float("nan"), dtype=torch.float16,
                                        device=dev))
         if wl.T > 1:

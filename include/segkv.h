@@ -271,13 +271,18 @@ size_t segkv_workspace_bytes(const segkv_dims* d);
  * Placement hint for the caller's allocator (Section 3.2 leaves the relative
  * placement of the K and V buffers open).  Returns the number of bytes by which
  * the base addresses of prompt_v / resp_v should differ from those of prompt_k /
- * resp_k modulo 1024 for the kernel these dimensions select (for example: K
- * buffers 1024-byte aligned, V buffers at a 1024-byte aligned address plus this
- * value).  On MI355X one in four 256-byte address classes is served more slowly;
- * when every work-group streams a single 256-byte column of K and of V the
- * stagger keeps any KV head from drawing both from the slow class.  Purely a
- * performance hint (measured 3% on the Llama2-70B shape): results never depend
- * on it, and 0 is returned where it does not help.  Host-only.
+ * resp_k modulo 8192 for the kernel these dimensions select (for example: K
+ * buffers 8192-byte aligned, V buffers at an 8192-byte aligned address plus this
+ * value).  Two things were measured on MI355X.  One in four 256-byte address
+ * classes is served more slowly; when every work-group streams a single 256-byte
+ * column of K and of V, an offset of 256 modulo 1024 keeps any KV head from
+ * drawing both from the slow class (3-5 % on the Llama2-7B and 70B shapes).  And a
+ * wave asks for row i of K and row i of V at the same moment; when the bytes of
+ * one token's keys are a power of two, a further 4096 puts the two in different
+ * places of the memory system (1.4 % on the Llama2-7B shape, 0.6 % on the 70B
+ * shape, nothing where a token's keys are not a power of two bytes).  Purely a
+ * performance hint: results never depend on it, and 0 is returned where it does
+ * not help (heads of 512 bytes).  Host-only.
  */
 size_t segkv_value_stagger_bytes(const segkv_dims* d);
 

@@ -361,9 +361,10 @@ size_t segkv_workspace_bytes(const segkv_dims* d)
 size_t segkv_value_stagger_bytes(const segkv_dims* d)
 {
     if (!dims_ok(d) || !dims_supported(d)) return 0;
-    // only the per-head column streams of the matrix-core kernel gain from it
+    // only the per-head column streams of the matrix-core kernel gain from it:
+    // 256 to step off the slow address class, 4096 to part row i of K from row i of V
     const Plan pl = make_plan(d);
-    return (pl.mfma && pl.D * 2 == 256) ? 256 : 0;
+    return (pl.mfma && pl.D * 2 == 256) ? 4096 + 256 : 0;
 }
 
 int segkv_append_kv(void* resp_k, void* resp_v, const void* k_new, const void* v_new, int32_t t,

@@ -137,12 +137,12 @@ def test_probe_rejects_bad_arguments_without_a_device():
 
 
 def test_value_stagger_hint_is_host_only_and_bounded():
-    # a placement hint: a multiple of 16 below 1024, 0 for invalid dimensions
+    # a placement hint: a multiple of 16 below 8192, 0 for invalid dimensions
     for kw in (dict(B=32, beam=4, Hq=64, Hkv=8, D=128, Lp=2048, T=256, Tcap=256),
                dict(B=128, beam=1, Hq=32, Hkv=32, D=128, Lp=1024, T=128, Tcap=128),
                dict(B=1, beam=4, Hq=4, Hkv=4, D=64, Lp=32, T=8, Tcap=16)):
         v = segkv.value_stagger_bytes(segkv.make_dims(**kw))
-        assert 0 <= v < 1024 and v % 16 == 0
+        assert 0 <= v < 8192 and v % 16 == 0
     assert segkv.value_stagger_bytes(segkv.make_dims(B=0, beam=4, Hq=4, Hkv=4, D=64, Lp=32, T=8,
                                                      Tcap=16)) == 0
 
