@@ -40,13 +40,13 @@ MALL_BYTES = 256 << 20
 # script: every figure names the summary under profiles/ that holds it and the
 # commit whose kernel was profiled; a kernel changed since then needs a new profile.
 PROFILED_TRAFFIC = {
-    "llama2_7b_greedy": {"bytes": 2420526272, "profile": "profiles/sdpa_decode_mfma_llama2_7b_greedy.md", "kernel_commit": "455c74c"},
-    "llama2_70b_gqa": {"bytes": 309519445, "profile": "profiles/sdpa_decode_mfma_llama2_70b_gqa.md", "kernel_commit": "455c74c"},
-    "gptj6b": {"bytes": 307615806, "profile": "profiles/sdpa_decode_mfma_gptj6b.md", "kernel_commit": "455c74c"},
-    "bloom176b_alibi": {"bytes": 537434893, "profile": "profiles/sdpa_decode_mfma_bloom176b_alibi.md", "kernel_commit": "455c74c"},
-    "gptj6b_1024_1024": {"bytes": 1088735629, "profile": "profiles/sdpa_decode_mfma_gptj6b_1024_1024.md", "kernel_commit": "455c74c"},
-    "llama2_13b_1024_1024": {"bytes": 1358398337, "profile": "profiles/sdpa_decode_mfma_llama2_13b_1024_1024.md", "kernel_commit": "455c74c"},
-    "llama2_13b_bs8": {"bytes": 192379819, "profile": "profiles/sdpa_decode_mfma_llama2_13b_bs8.md", "kernel_commit": "455c74c"},
+    "llama2_7b_greedy": {"bytes": 2420529004, "profile": "profiles/sdpa_decode_mfma_llama2_7b_greedy.md", "kernel_commit": "cde399a"},
+    "llama2_70b_gqa": {"bytes": 309474961, "profile": "profiles/sdpa_decode_mfma_llama2_70b_gqa.md", "kernel_commit": "cde399a"},
+    "gptj6b": {"bytes": 307609518, "profile": "profiles/sdpa_decode_mfma_gptj6b.md", "kernel_commit": "cde399a"},
+    "bloom176b_alibi": {"bytes": 537425832, "profile": "profiles/sdpa_decode_mfma_bloom176b_alibi.md", "kernel_commit": "cde399a"},
+    "gptj6b_1024_1024": {"bytes": 1088715927, "profile": "profiles/sdpa_decode_mfma_gptj6b_1024_1024.md", "kernel_commit": "cde399a"},
+    "llama2_13b_1024_1024": {"bytes": 1358428767, "profile": "profiles/sdpa_decode_mfma_llama2_13b_1024_1024.md", "kernel_commit": "cde399a"},
+    "llama2_13b_bs8": {"bytes": 192381079, "profile": "profiles/sdpa_decode_mfma_llama2_13b_bs8.md", "kernel_commit": "cde399a"},
 }
 MIN_TIMED_REGION_S = 0.05      # short kernels are launched often enough to fill this
 MAX_TIMED_LAUNCHES = 4000
