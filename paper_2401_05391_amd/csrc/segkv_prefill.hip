@@ -19,6 +19,7 @@
 // tiles through registers (D = 64, 256); sdpa_prefill_direct_kernel (D = 128)
 // copies them from global memory straight into LDS, three tiles deep.
 #include <cstdlib>
+#include <type_traits>
 #include "segkv_common.h"
 #include "segkv_launch.h"
 #include "segkv_device.h"
@@ -262,7 +263,17 @@ __device__ __forceinline__ void copy16_to_lds(const _Float16* gptr, unsigned lds
                  : "memory");
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+// The same with a uniform base address in scalar registers and a 32-bit byte offset per lane.
+__device__ __forceinline__ void copy16_to_lds(const _Float16* base, uint32_t byte_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(byte_off), "s"(base), "s"(lds_base)
+                 : "memory");
+}
+
+// (Three work-groups per CU: the register budget of three waves per SIMD is part of the design.)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))
 void sdpa_prefill_direct_kernel(PrefillParams p)
 {
     constexpr int D = 128;
@@ -305,20 +316,40 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)s_stage;
     const int crow = lane / CPR;                          // row within the instruction's 4
     const int cpos = lane % CPR;                          // chunk position filled by this lane
-    auto issue = [&](int ti, int stage) __attribute__((always_inline)) {
-        const int base = ti * kKeyTile;
-        const int lim = min(kKeyTile - 1, p.N0 - 1 - base);
-        const size_t tile_off = (((size_t)b * p.N0 + base) * p.Hkv + g) * D;
-        const unsigned sbase = lds0 + stage * STAGEB;
+    // A lane's byte offset within a tile is fixed (row, permuted chunk); the tile's base
+    // address is uniform and travels in scalar registers, one tile stride further per turn.
+    auto chunk_k = [&](int r) __attribute__((always_inline)) { return cpos ^ (r & (CPR - 1)); };
+    auto chunk_v = [&](int r) __attribute__((always_inline)) {
+        return (((cpos >> 1) ^ (r & 7)) << 1) | (cpos & 1);
+    };
+    uint32_t lane_off_k[INS_PER_WAVE], lane_off_v[INS_PER_WAVE];
 #pragma unroll
-        for (int j = 0; j < INS_PER_WAVE; ++j) {
-            const int i = wave * INS_PER_WAVE + j;
-            const int r = RPI * i + crow;
-            const uint32_t roff = (uint32_t)min(r, lim) * row_stride;
-            const int ck = cpos ^ (r & (CPR - 1));
-            const int cv = (((cpos >> 1) ^ (r & 7)) << 1) | (cpos & 1);
-            copy16_to_lds(p.k + tile_off + roff + ck * 8, sbase + i * 1024);
-            copy16_to_lds(p.v + tile_off + roff + cv * 8, sbase + TILEB + i * 1024);
+    for (int j = 0; j < INS_PER_WAVE; ++j) {
+        const int r = RPI * (wave * INS_PER_WAVE + j) + crow;
+        lane_off_k[j] = ((uint32_t)r * row_stride + chunk_k(r) * 8) * 2;
+        lane_off_v[j] = ((uint32_t)r * row_stride + chunk_v(r) * 8) * 2;
+    }
+    const size_t head_off = ((size_t)b * p.N0 * p.Hkv + g) * D;
+    const size_t tile_stride = (size_t)kKeyTile * row_stride;
+    auto issue = [&](int ti, int stage) __attribute__((always_inline)) {
+        const int lim = p.N0 - 1 - ti * kKeyTile;         // last valid row of the tile
+        const _Float16* const k_tile = p.k + head_off + ti * tile_stride;
+        const _Float16* const v_tile = p.v + head_off + ti * tile_stride;
+        const unsigned sbase = lds0 + stage * STAGEB + wave * INS_PER_WAVE * 1024;
+        if (lim >= kKeyTile - 1) {
+#pragma unroll
+            for (int j = 0; j < INS_PER_WAVE; ++j) {
+                copy16_to_lds(k_tile, lane_off_k[j], sbase + j * 1024);
+                copy16_to_lds(v_tile, lane_off_v[j], sbase + TILEB + j * 1024);
+            }
+        } else {                                          // ragged last tile: rows past the end repeat the last one
+#pragma unroll
+            for (int j = 0; j < INS_PER_WAVE; ++j) {
+                const int r = RPI * (wave * INS_PER_WAVE + j) + crow;
+                const uint32_t roff = (uint32_t)min(r, lim) * row_stride;
+                copy16_to_lds(k_tile, (roff + chunk_k(r) * 8) * 2, sbase + j * 1024);
+                copy16_to_lds(v_tile, (roff + chunk_v(r) * 8) * 2, sbase + TILEB + j * 1024);
+            }
         }
     };
     issue(0, 0);
@@ -358,35 +389,32 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     const int vy = ((grp & 1) ^ (vrow & 7)) << 5;                      // V pair permutation
     const int tr_base = vrow * ROWB + 8 * (li & 3);
 
-    auto compute_tile = [&](const unsigned char* k_tile, const unsigned char* v_tile, int base,
-                            bool diagonal) __attribute__((always_inline)) {
-        float16_t s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.0f;
-#pragma unroll
-        for (int t = 0; t < NKS; ++t) {
-            const half8_t a =
-                *reinterpret_cast<const half8_t*>(k_tile + n * ROWB + (((2 * t + h) << 4) ^ kx));
-            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
-        }
-        // plain tiles keep the raw products in s and apply the scale inside the
-        // exponent's multiply-add; masked tiles finish their logits here
-        const bool plain = !diagonal && p.slopes == nullptr;
-        const float mult = plain ? scale2 : 1.0f;
-        float m_tile = -INFINITY;
-        if (plain) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) m_tile = fmaxf(m_tile, s[r]);
-            m_tile *= scale2;
-        } else {
+    // Lane-constant LDS addresses of the operand reads; the stage is a compile-time
+    // constant of each copy of the loop body below, so it travels in the instructions'
+    // immediate offsets and no address is computed per tile.
+    const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+
+    // Softmax of one tile and its P.V product.  s holds the raw products; tiles with a
+    // mask or a bias first bring their logits into the same raw units (bias divided by the
+    // scale, masked keys at minus infinity), so that one copy of the code below serves
+    // both and the scale is applied inside the exponent's multiply-add.
+    const float bias_raw = slope2 / scale2;
+    auto finish_tile = [&](float16_t& s, int base, bool plain, int SOFF) __attribute__((always_inline)) {
+        if (!plain) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = base + 8 * (r >> 2) + 4 * h + (r & 3);
-                const float z = s[r] * scale2 + slope2 * (float)(key - qi);
-                s[r] = (key <= qi) ? z : -INFINITY;
-                m_tile = fmaxf(m_tile, s[r]);
+                const float z = s[r] + bias_raw * (float)(key - qi);
+                s[r] = (key <= qi) ? z : -INFINITY;       // causal; also hides keys >= N0
             }
         }
+        float m_tile = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) m_tile = fmaxf(m_tile, s[r]);
+        m_tile *= scale2;
+        const float mult = scale2;
+        // The two lanes that share a query see different keys, but the vote is wave-wide:
+        // their maxima are only exchanged when the reference moves.
         if (__any(m_tile > m_ref + kRescaleSlack)) {
             m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
             const float m_new = fmaxf(m_ref, m_tile);
@@ -400,38 +428,56 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         }
         half8_t pb[2];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float pr = fast_exp2(__builtin_fmaf(s[r], mult, -m_ref));
-            l_part += pr;
-            pb[r >> 3][r & 7] = (_Float16)pr;
+        for (int r = 0; r < 16; r += 2) {
+            const float p0 = fast_exp2(__builtin_fmaf(s[r], mult, -m_ref));
+            const float p1 = fast_exp2(__builtin_fmaf(s[r + 1], mult, -m_ref));
+            const half2_t pp = {(_Float16)p0, (_Float16)p1};
+            // the row sum adds what the P.V product will see: the rounded pair, in one instruction
+            l_part = __builtin_amdgcn_fdot2(pp, ones, l_part, false);
+            pb[r >> 3][r & 7] = pp.x;
+            pb[r >> 3][(r & 7) + 1] = pp.y;
         }
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const int off = tr_base + (16 * u) * ROWB + ((db * 64) ^ vy);
-                const half4_t lo = lds_read_tr16(v_tile + off);
-                const half4_t hi = lds_read_tr16(v_tile + off + 8 * ROWB);
+                const int off = SOFF + TILEB + tr_base + (16 * u) * ROWB + ((db * 64) ^ vy);
+                const half4_t lo = lds_read_tr16(s_stage + off);
+                const half4_t hi = lds_read_tr16(s_stage + off + 8 * ROWB);
                 const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
             }
         }
     };
 
-    // ---- main loop: tile ti is computed while ti+1 and ti+2 are on their way.
-    // s_waitcnt immediates: vmcnt in bits 3:0, no wait on the other counters. ----
-    int stage = 0;
-    for (int ti = 0; ti < n_tiles; ++ti) {
+    // ---- one turn of the main loop: tile ti is computed out of stage STAGE while ti+1
+    // and ti+2 are on their way.  s_waitcnt immediates: vmcnt in bits 3:0, no wait on the
+    // other counters. ----
+    const bool alibi = p.slopes != nullptr;
+    auto turn = [&](int ti, int STAGE) __attribute__((always_inline)) {
+        const int SOFF = STAGE * STAGEB;
         // this wave's copies of tile ti have landed (the 2 * INS_PER_WAVE newest belong to ti+1)
         if (ti + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * INS_PER_WAVE));
         else                  __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();      // everybody's have; and everybody is done with tile ti-1's stage
-        if (ti + 2 < n_tiles) issue(ti + 2, stage == 0 ? 2 : stage - 1);
+        if (ti + 2 < n_tiles) issue(ti + 2, STAGE == 0 ? 2 : STAGE - 1);
         const int base = ti * kKeyTile;
         if (base <= wq0 + kQueryTile - 1) {
-            const unsigned char* const k_tile = s_stage + stage * STAGEB;
-            compute_tile(k_tile, k_tile + TILEB, base, base + kKeyTile - 1 > wq0);
+            float16_t s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+#pragma unroll
+            for (int t = 0; t < NKS; ++t) {
+                const half8_t a = *reinterpret_cast<const half8_t*>(
+                    s_stage + SOFF + n * ROWB + (((2 * t + h) << 4) ^ kx));
+                s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
+            }
+            finish_tile(s, base, !alibi && base + kKeyTile - 1 <= wq0, SOFF);
         }
+    };
+    int stage = 0;
+    for (int ti = 0; ti < n_tiles; ++ti) {
+        turn(ti, stage);
         stage = stage == NSTAGE - 1 ? 0 : stage + 1;
     }
     __syncthreads();
@@ -472,7 +518,8 @@ hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
     const unsigned grid = (unsigned)((size_t)p.B * p.Hq * n_qblocks);
     const dim3 block(nw * 64);
     // the test-only override keeps the register-staged kernel at D = 128
-    const bool direct = D == 128 && !tuning().prefill_regs;
+    // (The direct kernel divides the bias by the scale: a zero scale goes the other way.)
+    const bool direct = D == 128 && !tuning().prefill_regs && p.scale2 != 0.0f;
     switch (D) {
         case 64:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, st, p);
         case 128:
