@@ -392,6 +392,19 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     // Lane-constant LDS addresses of the operand reads; the stage is a compile-time
     // constant of each copy of the loop body below, so it travels in the instructions'
     // immediate offsets and no address is computed per tile.
+    // (finished values the compiler may not take apart again into a shared base plus a part
+    // that it would then add back before every read)
+    int k_addr[NKS], v_addr[NDB];
+#pragma unroll
+    for (int t = 0; t < NKS; ++t) {
+        k_addr[t] = n * ROWB + (((2 * t + h) << 4) ^ kx);
+        asm volatile("" : "+v"(k_addr[t]));
+    }
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+        v_addr[db] = TILEB + tr_base + ((db * 64) ^ vy);
+        asm volatile("" : "+v"(v_addr[db]));
+    }
     const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
 
     // Softmax of one tile and its P.V product.  s holds the raw products; tiles with a
@@ -399,7 +412,8 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     // scale, masked keys at minus infinity), so that one copy of the code below serves
     // both and the scale is applied inside the exponent's multiply-add.
     const float bias_raw = slope2 / scale2;
-    auto finish_tile = [&](float16_t& s, int base, bool plain, int SOFF) __attribute__((always_inline)) {
+    auto finish_tile = [&](float16_t& s, int base, bool plain, auto stage_c) __attribute__((always_inline)) {
+        constexpr int SOFF = decltype(stage_c)::value * STAGEB;
         if (!plain) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -441,9 +455,8 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         for (int db = 0; db < NDB; ++db) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const int off = SOFF + TILEB + tr_base + (16 * u) * ROWB + ((db * 64) ^ vy);
-                const half4_t lo = lds_read_tr16(s_stage + off);
-                const half4_t hi = lds_read_tr16(s_stage + off + 8 * ROWB);
+                const half4_t lo = lds_read_tr16(s_stage + v_addr[db] + (SOFF + (16 * u) * ROWB));
+                const half4_t hi = lds_read_tr16(s_stage + v_addr[db] + (SOFF + (16 * u + 8) * ROWB));
                 const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
             }
@@ -454,13 +467,14 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     // and ti+2 are on their way.  s_waitcnt immediates: vmcnt in bits 3:0, no wait on the
     // other counters. ----
     const bool alibi = p.slopes != nullptr;
-    auto turn = [&](int ti, int STAGE) __attribute__((always_inline)) {
-        const int SOFF = STAGE * STAGEB;
+    auto turn = [&](int ti, auto stage_c) __attribute__((always_inline)) {
+        constexpr int STAGE = decltype(stage_c)::value;
+        constexpr int SOFF = STAGE * STAGEB;
         // this wave's copies of tile ti have landed (the 2 * INS_PER_WAVE newest belong to ti+1)
         if (ti + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * INS_PER_WAVE));
         else                  __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();      // everybody's have; and everybody is done with tile ti-1's stage
-        if (ti + 2 < n_tiles) issue(ti + 2, STAGE == 0 ? 2 : STAGE - 1);
+        if (ti + 2 < n_tiles) issue(ti + 2, (STAGE + 2) % NSTAGE);
         const int base = ti * kKeyTile;
         if (base <= wq0 + kQueryTile - 1) {
             float16_t s;
@@ -468,17 +482,17 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
             for (int r = 0; r < 16; ++r) s[r] = 0.0f;
 #pragma unroll
             for (int t = 0; t < NKS; ++t) {
-                const half8_t a = *reinterpret_cast<const half8_t*>(
-                    s_stage + SOFF + n * ROWB + (((2 * t + h) << 4) ^ kx));
+                const half8_t a = *reinterpret_cast<const half8_t*>(s_stage + k_addr[t] + SOFF);
                 s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
             }
-            finish_tile(s, base, !alibi && base + kKeyTile - 1 <= wq0, SOFF);
+            finish_tile(s, base, !alibi && base + kKeyTile - 1 <= wq0, stage_c);
         }
     };
-    int stage = 0;
-    for (int ti = 0; ti < n_tiles; ++ti) {
-        turn(ti, stage);
-        stage = stage == NSTAGE - 1 ? 0 : stage + 1;
+    // (one copy of the loop body per stage: the stage's LDS offset is an immediate)
+    for (int ti = 0; ti < n_tiles; ti += NSTAGE) {
+        turn(ti, std::integral_constant<int, 0>{});
+        if (ti + 1 < n_tiles) turn(ti + 1, std::integral_constant<int, 1>{});
+        if (ti + 2 < n_tiles) turn(ti + 2, std::integral_constant<int, 2>{});
     }
     __syncthreads();
 
