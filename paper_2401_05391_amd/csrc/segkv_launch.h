@@ -82,6 +82,7 @@ struct PrefillParams {
     const float* slopes;  // [Hq] or null
     float scale2;         // scale * log2(e)
     int B, N0, Hq, Hkv, G;
+    int heads_per_group;  // work order: query heads whose blocks are dealt long-first together (set by the launcher)
 };
 
 struct RopeParams {

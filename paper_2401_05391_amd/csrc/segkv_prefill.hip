@@ -18,6 +18,7 @@
 // are scheduled first.  Two kernels: sdpa_prefill_mfma_kernel<D> stages the
 // tiles through registers (D = 64, 256); sdpa_prefill_direct_kernel (D = 128)
 // copies them from global memory straight into LDS, three tiles deep.
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 #include "segkv_common.h"
@@ -32,6 +33,52 @@ namespace segkv {
 // work.  D = 256: eight -- the accumulators leave room for two waves per SIMD
 // only within one work-group's LDS, and K/V tiles are shared by twice the queries.
 constexpr int prefill_waves(int D) { return D <= 128 ? 4 : 8; }
+
+// Work order.  The query blocks of one (request, query head) re-read the same K/V rows
+// (block j needs keys 0 .. its own end), so they should run on one XCD at about the same
+// time: the re-reads are then served by its L2 instead of HBM.  Later blocks have more keys
+// to visit, and a long block that starts last leaves most of the chip idle while it
+// finishes.  Both are met as follows.  The heads are split evenly among the 8 XCDs (the
+// hardware sends work-group i to XCD i mod 8; the grid is padded to 8 equal shares and the
+// surplus work-groups leave at once).  Each XCD takes its heads in groups of about as many
+// as fill its work-group slots once (heads_per_group x blocks per head), and deals each
+// group's blocks longest first ACROSS the group's heads: what runs together still belongs
+// to those few heads, and every group -- the XCD's last one too -- ends with its shortest
+// blocks.  Heads that share a KV head (grouped queries) are neighbours within a group.
+struct PrefillWorkItem { int b, hq, qblk; bool valid; };
+__host__ __device__ inline int prefill_grid_size(int n_heads, int n_qblocks)
+{
+    return kNumXcd * ((n_heads + kNumXcd - 1) / kNumXcd) * n_qblocks;
+}
+__device__ __forceinline__ PrefillWorkItem prefill_work_item(const PrefillParams& p, int n_qblocks)
+{
+    const int xcd = blockIdx.x % kNumXcd;
+    const int k = blockIdx.x / kNumXcd;                        // this XCD's k-th work-group
+    const int n_heads = p.B * p.Hq;
+    const int heads_lo = n_heads / kNumXcd, rem = n_heads % kNumXcd;
+    const int first_head = xcd * heads_lo + min(xcd, rem);     // the XCD's heads
+    const int heads_x = heads_lo + (xcd < rem ? 1 : 0);
+    if (k >= heads_x * n_qblocks) return {0, 0, 0, false};
+    // groups of nearly equal size, about heads_per_group heads each
+    const int n_groups = max(1, (heads_x + p.heads_per_group / 2) / p.heads_per_group);
+    const int small = heads_x / n_groups, n_big = heads_x % n_groups;   // n_big groups hold small + 1
+    const int big_items = (small + 1) * n_qblocks;
+    int group_first, heads_here, r;
+    if (k < n_big * big_items) {
+        const int gi = k / big_items;
+        r = k - gi * big_items;
+        heads_here = small + 1;
+        group_first = gi * (small + 1);
+    } else {
+        const int k2 = k - n_big * big_items;
+        const int gi = k2 / (small * n_qblocks);
+        r = k2 - gi * (small * n_qblocks);
+        heads_here = small;
+        group_first = n_big * (small + 1) + gi * small;
+    }
+    const int head = first_head + group_first + r % heads_here;
+    return {head / p.Hq, head % p.Hq, n_qblocks - 1 - r / heads_here, true};
+}
 
 // Two work-groups per CU (two waves per SIMD) for D <= 128, so that one wave's
 // softmax arithmetic overlaps the other's MFMAs.
@@ -64,30 +111,40 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
     const int n = lane & 31;
     const int h = lane >> 5;
 
-    // ---- work item.  The query blocks of one (request, query head) re-read the
-    // same K/V rows (block j needs keys 0 .. 128 (j+1)), so they are neighbours in
-    // the work order and run on one XCD at about the same time: the re-reads are
-    // served by its L2 instead of HBM.  Within a head the long (late) blocks come
-    // first; heads that share a KV head (grouped queries) are neighbours too. ----
+    // ---- work item (see prefill_work_item for the order) ----
     const int n_qblocks = (p.N0 + kPrefillQueries - 1) / kPrefillQueries;
-    int id = xcd_contiguous_index(blockIdx.x, gridDim.x);
-    const int qblk = n_qblocks - 1 - id % n_qblocks;   id /= n_qblocks;
-    const int hq = id % p.Hq;                          id /= p.Hq;
-    const int b = id;
+    const PrefillWorkItem item = prefill_work_item(p, n_qblocks);
+    if (!item.valid) return;                  // padding of the grid: the whole work-group leaves
+    const int qblk = item.qblk, hq = item.hq, b = item.b;
     const int g = hq / p.G;
     const int q0 = qblk * kPrefillQueries;
     const int wq0 = q0 + wave * kQueryTile;   // first query token of this wave
     const int qi = wq0 + n;                   // this lane's query token
     const float slope2 = p.slopes ? p.slopes[hq] * kLog2e : 0.0f;
+    // the scale enters as |scale| (its sign is moved into Q), so that the maximum of
+    // the raw products of a tile is the maximum of its scaled logits
+    const float scale2 = fabsf(p.scale2);
+    // Logits are kept in the units of the raw products, raw + bias / |scale|, and the scale is
+    // applied inside the exponent's multiply-add.  A zero scale leaves only the bias: then
+    // every tile takes the masked path, which drops the product (raw_w = 0) and keeps the
+    // bias in final units (mult = 1).
+    const bool zero_scale = scale2 == 0.0f;
+    const float raw_w = zero_scale ? 0.0f : 1.0f;
+    const float bias_raw = zero_scale ? slope2 : slope2 / scale2;
+    const float mult = zero_scale ? 1.0f : scale2;
 
     // ---- Q^T operand: this lane's query row, 8 halves per k-step, in registers ----
     half8_t qreg[NKS];
     {
         const int qrow = min(qi, p.N0 - 1);
         const _Float16* qp = p.q + (((size_t)b * p.N0 + qrow) * p.Hq + hq) * D;
+        const uint32_t flip = p.scale2 < 0.0f ? 0x80008000u : 0u;
 #pragma unroll
-        for (int t = 0; t < NKS; ++t)
-            qreg[t] = __builtin_bit_cast(half8_t, load16(qp + 16 * t + 8 * h));
+        for (int t = 0; t < NKS; ++t) {
+            u32x4_t w = load16(qp + 16 * t + 8 * h);
+            w.x ^= flip; w.y ^= flip; w.z ^= flip; w.w ^= flip;
+            qreg[t] = __builtin_bit_cast(half8_t, w);
+        }
     }
 
     // ---- cooperative K/V tile staging ----
@@ -95,19 +152,34 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
     const int n_tiles = (k_end + kKeyTile - 1) / kKeyTile;
     const uint32_t row_stride = (uint32_t)p.Hkv * D;
     u32x4_t sk[kVecPerThread], sv[kVecPerThread];
+    // a thread's offsets within a tile are fixed; the tile's base address is uniform
+    uint32_t lane_off[kVecPerThread];
+#pragma unroll
+    for (int c = 0; c < kVecPerThread; ++c) {
+        const int i = tid + c * NT;
+        lane_off[c] = (uint32_t)((i / CPR) % kKeyTile) * row_stride + (i % CPR) * 8;
+    }
     auto fetch = [&](int ti) __attribute__((always_inline)) {
         const int base = ti * kKeyTile;
-        const int lim = min(kKeyTile - 1, p.N0 - 1 - base);
+        const int lim = p.N0 - 1 - base;                   // last valid row of the tile
         const size_t tile_off = (((size_t)b * p.N0 + base) * p.Hkv + g) * D;
         const _Float16* const kb = p.k + tile_off;
         const _Float16* const vb = p.v + tile_off;
+        if (lim >= kKeyTile - 1) {
 #pragma unroll
-        for (int c = 0; c < kVecPerThread; ++c) {
-            const int i = tid + c * NT;
-            const int row = min((i / CPR) % kKeyTile, lim);
-            const uint32_t off = (uint32_t)row * row_stride + (i % CPR) * 8;
-            sk[c] = load16(kb + off);
-            sv[c] = load16(vb + off);
+            for (int c = 0; c < kVecPerThread; ++c) {
+                sk[c] = load16(kb + lane_off[c]);
+                sv[c] = load16(vb + lane_off[c]);
+            }
+        } else {                                           // ragged last tile: rows past the end repeat the last one
+#pragma unroll
+            for (int c = 0; c < kVecPerThread; ++c) {
+                const int i = tid + c * NT;
+                const int row = min((i / CPR) % kKeyTile, lim);
+                const uint32_t off = (uint32_t)row * row_stride + (i % CPR) * 8;
+                sk[c] = load16(kb + off);
+                sv[c] = load16(vb + off);
+            }
         }
     };
     auto stage = [&](int buf) __attribute__((always_inline)) {
@@ -146,22 +218,21 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
                 *reinterpret_cast<const half8_t*>(k_tile + n * ROWB + ((2 * t + h) << 4));
             s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
         }
-        float m_tile = -INFINITY;
-        if (!diagonal && p.slopes == nullptr) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s[r] *= p.scale2;
-                m_tile = fmaxf(m_tile, s[r]);
-            }
-        } else {
+        // s holds the raw products; tiles with a mask or a bias bring their logits into the
+        // same raw units (bias divided by the scale, masked keys at minus infinity), and the
+        // scale is applied inside the exponent's multiply-add
+        if (diagonal || p.slopes != nullptr || zero_scale) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = base + 8 * (r >> 2) + 4 * h + (r & 3);
-                const float z = s[r] * p.scale2 + slope2 * (float)(key - qi);
+                const float z = __builtin_fmaf(s[r], raw_w, bias_raw * (float)(key - qi));
                 s[r] = (key <= qi) ? z : -INFINITY;       // causal; also hides keys >= N0
-                m_tile = fmaxf(m_tile, s[r]);
             }
         }
+        float m_tile = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) m_tile = fmaxf(m_tile, s[r]);
+        m_tile *= mult;
         // The two lanes that share a query (keys 4h..) see different keys, but the
         // vote is wave-wide: their maxima are only exchanged when the reference moves.
         if (__any(m_tile > m_ref + kRescaleSlack)) {
@@ -176,11 +247,16 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
                 for (int r = 0; r < 16; ++r) o_acc[db][r] *= corr;
         }
         half8_t pb[2];
+        const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float pr = fast_exp2(s[r] - m_ref);
-            l_part += pr;
-            pb[r >> 3][r & 7] = (_Float16)pr;
+        for (int r = 0; r < 16; r += 2) {
+            const float p0 = fast_exp2(__builtin_fmaf(s[r], mult, -m_ref));
+            const float p1 = fast_exp2(__builtin_fmaf(s[r + 1], mult, -m_ref));
+            const half2_t pp = {(_Float16)p0, (_Float16)p1};
+            // the row sum adds what the P.V product will see: the rounded pair, in one instruction
+            l_part = __builtin_amdgcn_fdot2(pp, ones, l_part, false);
+            pb[r >> 3][r & 7] = pp.x;
+            pb[r >> 3][(r & 7) + 1] = pp.y;
         }
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
@@ -295,10 +371,9 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     const int h = lane >> 5;
 
     const int n_qblocks = (p.N0 + kQueries - 1) / kQueries;
-    int id = xcd_contiguous_index(blockIdx.x, gridDim.x);
-    const int qblk = n_qblocks - 1 - id % n_qblocks;   id /= n_qblocks;
-    const int hq = id % p.Hq;                          id /= p.Hq;
-    const int b = id;
+    const PrefillWorkItem item = prefill_work_item(p, n_qblocks);
+    if (!item.valid) return;                  // padding of the grid: the whole work-group leaves
+    const int qblk = item.qblk, hq = item.hq, b = item.b;
     const int g = hq / p.G;
     const int q0 = qblk * kQueries;
     const int wq0 = q0 + wave * kQueryTile;
@@ -529,17 +604,22 @@ hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
     if (D != 64 && D != 128 && D != 256) return hipErrorInvalidValue;
     const int nw = prefill_waves(D);
     const int n_qblocks = (p.N0 + nw * kQueryTile - 1) / (nw * kQueryTile);
-    const unsigned grid = (unsigned)((size_t)p.B * p.Hq * n_qblocks);
+    const unsigned grid = (unsigned)prefill_grid_size(p.B * p.Hq, n_qblocks);
     const dim3 block(nw * 64);
+    // work-group slots of one XCD (32 CUs; work-groups per CU as the kernels' registers and
+    // LDS allow: 4 / 3 / 1 at D = 64 / 128 / 256) filled once by a group of heads
+    PrefillParams q = p;
+    const int slots_per_xcd = 32 * (D == 64 ? 4 : D == 128 ? 3 : 1);
+    q.heads_per_group = std::max(1, slots_per_xcd / n_qblocks);
     // the test-only override keeps the register-staged kernel at D = 128
     // (The direct kernel divides the bias by the scale: a zero scale goes the other way.)
     const bool direct = D == 128 && !tuning().prefill_regs && p.scale2 != 0.0f;
     switch (D) {
-        case 64:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, st, p);
+        case 64:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, st, q);
         case 128:
-            if (direct) return SEGKV_LAUNCH(sdpa_prefill_direct_kernel, dim3(grid), block, st, p);
-            return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, st, p);
-        default:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, st, p);
+            if (direct) return SEGKV_LAUNCH(sdpa_prefill_direct_kernel, dim3(grid), block, st, q);
+            return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, st, q);
+        default:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, st, q);
     }
 }
 

@@ -59,6 +59,25 @@ def test_prefill_matches_oracle(B, N0, Hq, Hkv, D, alibi, staging, planner_env):
     assert_parity(got, ref, f"prefill N0={N0} D={D}")
 
 
+@pytest.mark.parametrize("staging", ["direct", "regs"])
+@pytest.mark.parametrize("D,scale,alibi", [(128, -0.11, False), (128, 0.0, True), (128, 0.0, False),
+                                           (64, -0.2, True), (256, -0.07, False), (64, 0.0, True)])
+def test_prefill_negative_and_zero_scale(D, scale, alibi, staging, planner_env):
+    # the kernels keep the logits in the units of the raw products and move the sign of
+    # the scale into Q; a zero scale leaves only the bias (uniform weights without one)
+    from oracle import segkv_oracle as oracle
+    if staging == "regs" and D != 128:
+        pytest.skip("one kernel only at this head dimension")
+    planner_env(SEGKV_PREFILL=staging)
+    B, N0, Hq, Hkv = 2, 150, 4, 2
+    print(f"\n[case] prefill scale={scale} D={D} alibi={alibi} {staging}", flush=True)
+    q, k, v = _draw(B, N0, Hq, Hkv, D, 77)
+    slopes = alibi_slopes(Hq) if alibi else None
+    ref = oracle.sdpa_prefill(q, k, v, scale, slopes=slopes)
+    got = _run(q, k, v, scale, slopes)
+    assert_parity(got, ref, f"prefill scale={scale} D={D}")
+
+
 def test_prefill_is_deterministic_and_ignores_future_keys():
     q, k, v = _draw(2, 200, 4, 2, 128, 7)
     a = _run(q, k, v, 0.088)
