@@ -391,6 +391,35 @@ def prefill_rows(steps, warmup, segkv, torch):
     return rows
 
 
+def mfma_sustained_rates(segkv, torch):
+    """What the matrix cores sustain on register-resident operands (segkv_probe_mfma_rate): a
+    chain of the fp16 32x32x16 instruction on constant operands and on random ones.  The
+    random-operand rate is the ceiling the power limit leaves for prefill on real Q/K/V;
+    `roofline.peak` stays the published 2.5 PFLOP/s."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    n_groups, iters = 2048, 12000
+    out = torch.empty(n_groups * 256, dtype=torch.float32, device=dev)
+    clocks = torch.zeros(n_groups * 2, dtype=torch.int64, device=dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(3)
+    res = {}
+    for kind in ("constant", "random"):
+        if kind == "constant":
+            ops = torch.full((16 * 256 * 8,), 0.5, dtype=torch.float16, device=dev)
+        else:
+            ops = torch.randn(16 * 256 * 8, generator=g, device=dev, dtype=torch.float32).half()
+        call = [lambda: segkv.probe_mfma_rate(ops, out, clocks, n_groups, iters)]
+        call[0]()
+        ev_s, _ = timed_region(call, 3, torch)
+        c = clocks.cpu().numpy().reshape(n_groups, 2).astype(np.float64)
+        flop = n_groups * 4.0 * iters * 16 * 32768.0
+        res[kind + "_operands"] = {"tflops": flop / (ev_s / 3) / 1e12,
+                                   "clock_mhz": float(np.median(c[:, 0] / c[:, 1]) * 100.0)}
+        del ops
+    return res
+
+
 def prefill_bench(steps, warmup, segkv, torch):
     rows = prefill_rows(steps, warmup, segkv, torch)
     head = rows[0]
@@ -399,7 +428,8 @@ def prefill_bench(steps, warmup, segkv, torch):
             "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "f16", "data": "synthetic",
             "config": {"workload": head["workload"], **head["shape"]},
-            "roofline": head["roofline"], "cpu_baseline": None, "shapes": rows}
+            "roofline": head["roofline"], "cpu_baseline": None, "shapes": rows,
+            "mfma_sustained": mfma_sustained_rates(segkv, torch)}
 
 
 def fig6_rows(steps, warmup, segkv, torch):
@@ -594,6 +624,7 @@ def main():
                                                  "unique_response_rows", "roofline", "buffer_sets")})
     fig6 = None if a.no_extras else fig6_rows(a.steps, a.warmup, segkv, torch)
     prefill = None if a.no_extras else prefill_rows(max(a.steps // 4, 10), a.warmup, segkv, torch)
+    mfma_rates = None if a.no_extras else mfma_sustained_rates(segkv, torch)
 
     calibration = None
     if a.calibrate_counters:
@@ -634,8 +665,10 @@ def main():
             "sweep": fig6},
         "prefill": None if prefill is None else {
             "what": "segkv_sdpa_prefill (causal prompt attention, Section 3.3's special case) on the "
-                    "prompt shapes of the benchmark models; roofline: fp16 dense MFMA",
-            "shapes": prefill},
+                    "prompt shapes of the benchmark models; roofline: fp16 dense MFMA.  mfma_sustained: "
+                    "what a register-resident chain of the same matrix instruction reaches on this part "
+                    "with constant and with random operands (the power limit's ceiling for real Q/K/V)",
+            "shapes": prefill, "mfma_sustained": mfma_rates},
     }
     print(json.dumps(line), flush=True)
 

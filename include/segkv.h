@@ -307,6 +307,26 @@ const char* segkv_status_string(int status);
 void segkv_reload_tuning(void);
 
 /*
+ * MEASUREMENT ONLY (no attention arithmetic; nothing else in the library calls it).
+ * Runs a register-resident chain of the fp16 32x32x16 matrix instruction, the one the
+ * attention kernels use: n_groups work-groups of 4 waves, `iters` iterations of 16
+ * instructions per wave = n_groups * 4 * iters * 16 * 32768 flop in all.  The caller times
+ * the call (stream order) to get the rate the part sustains for the operands it supplied --
+ * constant ones run near the published clock, random ones under the power limit -- which is
+ * the practical ceiling for the prefill kernel's TFLOP/s.
+ *   operands  device, 16 * 256 * 16 bytes of fp16: 8 A then 8 B operands, 16 bytes per lane
+ *             of a 256-thread group (every group reads the same ones); 16-byte aligned
+ *   out       device, n_groups * 256 fp32 (sums of the accumulators, written so that the work
+ *             cannot be dropped)
+ *   clocks    device, n_groups * 2 uint64: shader cycles and 100 MHz ticks each group ran
+ *             (their ratio x 100 = its clock in MHz)
+ * Buffers stay the caller's; nothing is allocated.  Returns SEGKV_OK, SEGKV_INVALID_ARG (a
+ * null pointer, n_groups or iters <= 0, n_groups > 2^20), SEGKV_MISALIGNED or SEGKV_HIP_ERROR.
+ */
+int segkv_probe_mfma_rate(const void* operands, void* out, void* clocks, int32_t n_groups, int32_t iters,
+                          void* stream);
+
+/*
  * Prefill-phase attention (Section 3.1, prefill phase; Section 3.3: the special
  * case of the decode kernel that uses only the query and the prompt key/value).
  * Batch-first tensors in and out, no transposes:

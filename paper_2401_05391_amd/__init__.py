@@ -9,5 +9,5 @@ from .binding import (SegkvDims, SegkvError, append_kv, cache_segment_bytes,  # 
                       cache_standard_bytes, cache_token_bytes, grow_response, lineage_bytes,
                       lineage_update, load_library, sdpa_decode_lineage,
                       make_dims, prepare_sdpa_decode, response_capacity, rope_append, sdpa_decode, sdpa_decode_ragged,
-                      sdpa_decode_seq_first_prompt, sdpa_decode_static_scratch, sdpa_prefill,
+                      sdpa_decode_seq_first_prompt, sdpa_decode_static_scratch, sdpa_prefill, probe_mfma_rate,
                       status_string, stream_read_probe, value_stagger_bytes, workspace_bytes)

@@ -29,7 +29,7 @@ EXPORTS = ("segkv_append_kv", "segkv_sdpa_decode", "segkv_workspace_bytes",
            "segkv_grow_response", "segkv_sdpa_prefill", "segkv_value_stagger_bytes",
            "segkv_rope_append", "segkv_sdpa_decode_ragged", "segkv_sdpa_decode_seq_first_prompt",
            "segkv_lineage_bytes", "segkv_lineage_update", "segkv_sdpa_decode_lineage",
-           "segkv_sdpa_decode_static_scratch", "segkv_reload_tuning")
+           "segkv_sdpa_decode_static_scratch", "segkv_reload_tuning", "segkv_probe_mfma_rate")
 
 
 class SegkvDims(ctypes.Structure):
@@ -69,6 +69,8 @@ def load_library():
                                                      ctypes.c_float, dp, vp]
     lib.segkv_reload_tuning.restype = None
     lib.segkv_reload_tuning.argtypes = []
+    lib.segkv_probe_mfma_rate.restype = ctypes.c_int
+    lib.segkv_probe_mfma_rate.argtypes = [vp, vp, vp, i32, i32, vp]
     lib.segkv_sdpa_decode_ragged.restype = ctypes.c_int
     lib.segkv_sdpa_decode_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                                              ctypes.c_float, dp, vp]
@@ -271,6 +273,14 @@ def sdpa_prefill(out, q, k, v, dims: SegkvDims, scale: float, alibi_slopes=None,
                                            float(scale), ctypes.byref(dims), _stream_handle(stream))
     if rc != SEGKV_OK:
         raise SegkvError(rc, "segkv_sdpa_prefill")
+
+
+def probe_mfma_rate(operands, out, clocks, n_groups: int, iters: int, stream=None) -> None:
+    """Measurement only: a register-resident chain of the fp16 matrix instruction (see segkv.h)."""
+    rc = load_library().segkv_probe_mfma_rate(_ptr(operands), _ptr(out), _ptr(clocks), int(n_groups),
+                                              int(iters), _stream_handle(stream))
+    if rc != SEGKV_OK:
+        raise SegkvError(rc, "segkv_probe_mfma_rate")
 
 
 def cache_token_bytes(L: int, H: int, D: int, elem_bytes: int = 2) -> int:

@@ -12,7 +12,7 @@ LIB_DIR = os.path.join(_PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libsegkv.so")
 
 SOURCES = ["segkv_kernels.hip", "segkv_mfma.hip", "segkv_prefill.hip", "segkv_rope.hip",
-           "segkv_lineage.hip", "segkv_api.hip"]
+           "segkv_lineage.hip", "segkv_probe.hip", "segkv_api.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
     # keep hipcc from forming packed-fp32 instructions

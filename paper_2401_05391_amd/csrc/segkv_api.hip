@@ -612,6 +612,16 @@ int segkv_sdpa_prefill(void* out, const void* q, const void* k, const void* v,
     return hip_status(e);
 }
 
+int segkv_probe_mfma_rate(const void* operands, void* out, void* clocks, int32_t n_groups, int32_t iters,
+                          void* stream)
+{
+    if (!operands || !out || !clocks) return SEGKV_INVALID_ARG;
+    if (n_groups <= 0 || iters <= 0 || n_groups > (1 << 20)) return SEGKV_INVALID_ARG;
+    if (((uintptr_t)operands & 15u) || ((uintptr_t)out & 3u) || ((uintptr_t)clocks & 7u)) return SEGKV_MISALIGNED;
+    return hip_status(segkv::launch_mfma_rate_probe(operands, (float*)out, (unsigned long long*)clocks,
+                                                    n_groups, iters, (hipStream_t)stream));
+}
+
 uint64_t segkv_cache_token_bytes(int32_t L, int32_t H, int32_t D, int32_t elem_bytes)
 {
     if (L <= 0 || H <= 0 || D <= 0 || elem_bytes <= 0) return 0;

@@ -128,6 +128,8 @@ hipError_t launch_sdpa_decode(const SdpaParams& p, int D, int QB, int HP, unsign
 hipError_t launch_sdpa_decode_mfma(const SdpaParams& p, int D, int QT, int NW, unsigned grid,
                                    hipStream_t st);
 hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st);
+hipError_t launch_mfma_rate_probe(const void* operands, float* out, unsigned long long* clocks,
+                                  int n_groups, int iters, hipStream_t st);
 hipError_t launch_sdpa_merge(_Float16* out, const float* ws_ml, const float* ws_acc, int NQ, int D,
                              int n_chunks, hipStream_t st);
 hipError_t launch_append_kv(void* dst_k, void* dst_v, const void* src_k, const void* src_v,

@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2401_05391_amd as segkv
@@ -216,3 +217,29 @@ def test_workspace_size_and_static_scratch_limit_agree_over_random_dimensions():
             # partials are fp32: (m, l) pairs and D accumulators per query and chunk, at least two chunks
             assert need >= 2 * B * beam * Hkv * G * (D + 2) * 4
     assert seen_zero and seen_pos and seen_big
+
+
+@pytest.mark.gpu
+def test_mfma_rate_probe_runs_and_rejects_bad_arguments():
+    # the measurement helper: a short run writes finite sums and both clocks, twice the same
+    import torch
+    import paper_2401_05391_amd as segkv
+    from paper_2401_05391_amd.binding import SegkvError
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    ops = torch.randn(16 * 256 * 8, generator=g, device=dev, dtype=torch.float32).half()
+    out = torch.full((4 * 256,), float("nan"), dtype=torch.float32, device=dev)
+    clocks = torch.zeros(4 * 2, dtype=torch.int64, device=dev)
+    segkv.probe_mfma_rate(ops, out, clocks, 4, 10)
+    torch.cuda.synchronize()
+    first = out.cpu().numpy().copy()
+    assert np.all(np.isfinite(first)) and np.any(first != 0)
+    assert np.all(clocks.cpu().numpy() > 0)
+    segkv.probe_mfma_rate(ops, out, clocks, 4, 10)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), first)
+    with pytest.raises(SegkvError):
+        segkv.probe_mfma_rate(ops, out, clocks, 0, 10)
+    with pytest.raises(SegkvError):
+        segkv.probe_mfma_rate(ops, out, clocks, 4, 0)
