@@ -360,8 +360,6 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     constexpr int NINS = kKeyTile / RPI;                   // copy instructions per operand tile
     constexpr int NWAVES = 4, INS_PER_WAVE = NINS / NWAVES;
     constexpr int kQueries = NWAVES * kQueryTile;
-    constexpr int OROWB = D * 2 + 16;
-    static_assert(NWAVES * kQueryTile * OROWB <= NSTAGE * STAGEB, "output staging reuses the tiles");
     __shared__ __align__(256) unsigned char s_stage[NSTAGE * STAGEB];
 
     const int tid = threadIdx.x;
@@ -538,6 +536,38 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         }
     };
 
+    // ---- a wave's output, written from registers: the two lanes of a query hold alternating
+    // 8-byte pieces of its row; they swap every other piece, so that each stores 16 contiguous
+    // bytes.  No LDS and no barrier after the last tile.
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    auto store_output = [&]() __attribute__((always_inline)) {
+        const float l_row = l_part + __shfl_xor(l_part, 32);
+        const float inv = 1.0f / l_row;
+        _Float16* const row = p.out + (((size_t)b * p.N0 + min(qi, p.N0 - 1)) * p.Hq + hq) * D;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int ip = 0; ip < 4; ip += 2) {
+                uint32_t w[2][2];                      // [piece ip, ip + 1][its two words]
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const half2_t lo = {(_Float16)(o_acc[db][4 * (ip + j) + 0] * inv),
+                                        (_Float16)(o_acc[db][4 * (ip + j) + 1] * inv)};
+                    const half2_t hi = {(_Float16)(o_acc[db][4 * (ip + j) + 2] * inv),
+                                        (_Float16)(o_acc[db][4 * (ip + j) + 3] * inv)};
+                    w[j][0] = __builtin_bit_cast(uint32_t, lo);
+                    w[j][1] = __builtin_bit_cast(uint32_t, hi);
+                }
+                // upper-half lanes of the first operand <-> lower-half lanes of the second:
+                // lane n keeps its piece ip and receives lane n+32's piece ip (the next 8 bytes);
+                // lane n+32 receives lane n's piece ip+1 and keeps its own
+                const u32x2_t x0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                const u32x2_t x1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                const u32x4_t v = {x0.x, x1.x, x0.y, x1.y};
+                if (qi < p.N0) store16(row + 32 * db + 8 * (ip + h), v);
+            }
+    };
+
     // ---- one turn of the main loop: tile ti is computed out of stage STAGE while ti+1
     // and ti+2 are on their way.  s_waitcnt immediates: vmcnt in bits 3:0, no wait on the
     // other counters. ----
@@ -569,34 +599,7 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         if (ti + 1 < n_tiles) turn(ti + 1, std::integral_constant<int, 1>{});
         if (ti + 2 < n_tiles) turn(ti + 2, std::integral_constant<int, 2>{});
     }
-    __syncthreads();
-
-    // ---- normalise, transpose through LDS, store rows with 128-bit writes ----
-    l_part += __shfl_xor(l_part, 32);
-    const float inv = 1.0f / l_part;
-    unsigned char* const obuf = s_stage + wave * (kQueryTile * OROWB);
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            half4_t o4;
-            o4.x = (_Float16)(o_acc[db][4 * i + 0] * inv);
-            o4.y = (_Float16)(o_acc[db][4 * i + 1] * inv);
-            o4.z = (_Float16)(o_acc[db][4 * i + 2] * inv);
-            o4.w = (_Float16)(o_acc[db][4 * i + 3] * inv);
-            *reinterpret_cast<half4_t*>(obuf + n * OROWB + ((32 * db + 8 * i + 4 * h) << 1)) = o4;
-        }
-    wave_lds_exchange_point();                       // the wave reads back only what it wrote itself
-    constexpr int kRowsPerPass = 64 / CPR;
-#pragma unroll
-    for (int r0 = 0; r0 < kQueryTile; r0 += kRowsPerPass) {
-        const int row = r0 + lane / CPR;
-        const int ch = lane % CPR;
-        const int tok = wq0 + row;
-        const u32x4_t w = *reinterpret_cast<const u32x4_t*>(obuf + row * OROWB + (ch << 4));
-        if (tok < p.N0)
-            store16(p.out + (((size_t)b * p.N0 + tok) * p.Hq + hq) * D + ch * 8, w);
-    }
+    store_output();
 }
 
 hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
