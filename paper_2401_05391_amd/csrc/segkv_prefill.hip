@@ -348,18 +348,22 @@ __device__ __forceinline__ void copy16_to_lds(const _Float16* base, uint32_t byt
                  : "memory");
 }
 
-// (Three work-groups per CU: the register budget of three waves per SIMD is part of the design.)
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))
+// D = 128: four waves, three work-groups per CU (the register budget of three waves per SIMD
+// is part of the design).  D = 256: eight waves and one work-group per CU; rows are 512 bytes
+// and the same permutations act on the low four bits of the chunk index.
+constexpr int direct_waves(int D) { return D == 256 ? 8 : 4; }
+template <int D>
+__global__ __launch_bounds__(direct_waves(D) * 64) __attribute__((amdgpu_waves_per_eu(D == 256 ? 2 : 3)))
 void sdpa_prefill_direct_kernel(PrefillParams p)
 {
-    constexpr int D = 128;
     constexpr int CPR = D / 8, NKS = D / 16, NDB = D / 32;
     constexpr int ROWB = D * 2;                            // no padding: see above
     constexpr int TILEB = kKeyTile * ROWB, STAGEB = 2 * TILEB, NSTAGE = 3;
     constexpr int RPI = 64 / CPR;                          // rows per copy instruction
     constexpr int NINS = kKeyTile / RPI;                   // copy instructions per operand tile
-    constexpr int NWAVES = 4, INS_PER_WAVE = NINS / NWAVES;
+    constexpr int NWAVES = direct_waves(D), INS_PER_WAVE = NINS / NWAVES;
     constexpr int kQueries = NWAVES * kQueryTile;
+    static_assert(INS_PER_WAVE * NWAVES == NINS && INS_PER_WAVE >= 1, "the waves share a tile's copies evenly");
     __shared__ __align__(256) unsigned char s_stage[NSTAGE * STAGEB];
 
     const int tid = threadIdx.x;
@@ -391,7 +395,7 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     const int cpos = lane % CPR;                          // chunk position filled by this lane
     // A lane's byte offset within a tile is fixed (row, permuted chunk); the tile's base
     // address is uniform and travels in scalar registers, one tile stride further per turn.
-    auto chunk_k = [&](int r) __attribute__((always_inline)) { return cpos ^ (r & (CPR - 1)); };
+    auto chunk_k = [&](int r) __attribute__((always_inline)) { return cpos ^ (r & 15); };
     auto chunk_v = [&](int r) __attribute__((always_inline)) {
         return (((cpos >> 1) ^ (r & 7)) << 1) | (cpos & 1);
     };
@@ -457,7 +461,7 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
 
     const int grp = lane >> 4;
     const int li = lane & 15;
-    const int kx = (n & (CPR - 1)) << 4;                               // K chunk permutation of row n
+    const int kx = (n & 15) << 4;                                      // K chunk permutation of row n
     const int vrow = 4 * h + (li >> 2);                                // first V row of this lane
     const int vy = ((grp & 1) ^ (vrow & 7)) << 5;                      // V pair permutation
     const int tr_base = vrow * ROWB + 8 * (li & 3);
@@ -467,14 +471,17 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
     // immediate offsets and no address is computed per tile.
     // (finished values the compiler may not take apart again into a shared base plus a part
     // that it would then add back before every read)
-    int k_addr[NKS], v_addr[NDB];
+    // (The permutations touch address bits 4-7 only: k-step t + 8 and block db + 4 of a
+    // 512-byte row are their partners' addresses plus 256, one more immediate.)
+    constexpr int NKA = NKS < 8 ? NKS : 8, NVA = NDB < 4 ? NDB : 4;
+    int k_addr[NKA], v_addr[NVA];
 #pragma unroll
-    for (int t = 0; t < NKS; ++t) {
+    for (int t = 0; t < NKA; ++t) {
         k_addr[t] = n * ROWB + (((2 * t + h) << 4) ^ kx);
         asm volatile("" : "+v"(k_addr[t]));
     }
 #pragma unroll
-    for (int db = 0; db < NDB; ++db) {
+    for (int db = 0; db < NVA; ++db) {
         v_addr[db] = TILEB + tr_base + ((db * 64) ^ vy);
         asm volatile("" : "+v"(v_addr[db]));
     }
@@ -528,8 +535,8 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         for (int db = 0; db < NDB; ++db) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const half4_t lo = lds_read_tr16(s_stage + v_addr[db] + (SOFF + (16 * u) * ROWB));
-                const half4_t hi = lds_read_tr16(s_stage + v_addr[db] + (SOFF + (16 * u + 8) * ROWB));
+                const half4_t lo = lds_read_tr16(s_stage + v_addr[db % NVA] + (SOFF + (db / NVA) * 256 + (16 * u) * ROWB));
+                const half4_t hi = lds_read_tr16(s_stage + v_addr[db % NVA] + (SOFF + (db / NVA) * 256 + (16 * u + 8) * ROWB));
                 const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
             }
@@ -587,7 +594,7 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
             for (int r = 0; r < 16; ++r) s[r] = 0.0f;
 #pragma unroll
             for (int t = 0; t < NKS; ++t) {
-                const half8_t a = *reinterpret_cast<const half8_t*>(s_stage + k_addr[t] + SOFF);
+                const half8_t a = *reinterpret_cast<const half8_t*>(s_stage + k_addr[t % NKA] + (SOFF + (t / NKA) * 256));
                 s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
             }
             finish_tile(s, base, !alibi && base + kKeyTile - 1 <= wq0, stage_c);
@@ -605,7 +612,11 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
 hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
 {
     if (D != 64 && D != 128 && D != 256) return hipErrorInvalidValue;
-    const int nw = prefill_waves(D);
+    // tiles copied straight into LDS at D = 128 and 256 (a zero scale goes the other way: the
+    // direct kernels divide the bias by the scale); the test-only override keeps the
+    // register-staged kernels
+    const bool direct = (D == 128 || D == 256) && !tuning().prefill_regs && p.scale2 != 0.0f;
+    const int nw = direct ? direct_waves(D) : prefill_waves(D);
     const int n_qblocks = (p.N0 + nw * kQueryTile - 1) / (nw * kQueryTile);
     const unsigned grid = (unsigned)prefill_grid_size(p.B * p.Hq, n_qblocks);
     const dim3 block(nw * 64);
@@ -614,15 +625,14 @@ hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
     PrefillParams q = p;
     const int slots_per_xcd = 32 * (D == 64 ? 4 : D == 128 ? 3 : 1);
     q.heads_per_group = std::max(1, slots_per_xcd / n_qblocks);
-    // the test-only override keeps the register-staged kernel at D = 128
-    // (The direct kernel divides the bias by the scale: a zero scale goes the other way.)
-    const bool direct = D == 128 && !tuning().prefill_regs && p.scale2 != 0.0f;
     switch (D) {
         case 64:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, st, q);
         case 128:
-            if (direct) return SEGKV_LAUNCH(sdpa_prefill_direct_kernel, dim3(grid), block, st, q);
+            if (direct) return SEGKV_LAUNCH(sdpa_prefill_direct_kernel<128>, dim3(grid), block, st, q);
             return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<128>, dim3(grid), block, st, q);
-        default:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, st, q);
+        default:
+            if (direct) return SEGKV_LAUNCH(sdpa_prefill_direct_kernel<256>, dim3(grid), block, st, q);
+            return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<256>, dim3(grid), block, st, q);
     }
 }
 

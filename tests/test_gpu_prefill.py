@@ -36,6 +36,7 @@ CASES = [
     (1, 130, 4, 4, 128, True),
     (2, 257, 8, 2, 128, False),
     (1, 300, 2, 1, 256, False),
+    (2, 521, 4, 2, 256, True),
     (3, 128, 2, 2, 64, True),
     (1, 515, 2, 2, 128, False),
 ]
@@ -44,10 +45,10 @@ CASES = [
 @pytest.mark.parametrize("staging", ["direct", "regs"])
 @pytest.mark.parametrize("B,N0,Hq,Hkv,D,alibi", CASES)
 def test_prefill_matches_oracle(B, N0, Hq, Hkv, D, alibi, staging, planner_env):
-    # D = 128 has two kernels: tiles copied straight into LDS (the default) and
-    # tiles staged through registers (SEGKV_PREFILL=regs); other D ignore the knob
+    # D = 128 and 256 have two kernels: tiles copied straight into LDS (the default) and
+    # tiles staged through registers (SEGKV_PREFILL=regs); D = 64 ignores the knob
     from oracle import segkv_oracle as oracle
-    if staging == "regs" and D != 128:
+    if staging == "regs" and D == 64:
         pytest.skip("one kernel only at this head dimension")
     planner_env(SEGKV_PREFILL=staging)
     print(f"\n[case] prefill B={B} N0={N0} Hq={Hq} Hkv={Hkv} D={D} alibi={alibi}", flush=True)
@@ -66,7 +67,7 @@ def test_prefill_negative_and_zero_scale(D, scale, alibi, staging, planner_env):
     # the kernels keep the logits in the units of the raw products and move the sign of
     # the scale into Q; a zero scale leaves only the bias (uniform weights without one)
     from oracle import segkv_oracle as oracle
-    if staging == "regs" and D != 128:
+    if staging == "regs" and D == 64:
         pytest.skip("one kernel only at this head dimension")
     planner_env(SEGKV_PREFILL=staging)
     B, N0, Hq, Hkv = 2, 150, 4, 2
