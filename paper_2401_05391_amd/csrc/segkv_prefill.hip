@@ -592,10 +592,30 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
             float16_t s;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+            if constexpr (D == 256) {
+                // Two waves per SIMD here: an LDS read takes longer than the two MFMAs the
+                // compiler would leave between a read and its use, so the K operands run
+                // four reads ahead (the groups below fix that order).
+                constexpr int AHEAD = 3;
+                half8_t a[NKS];
 #pragma unroll
-            for (int t = 0; t < NKS; ++t) {
-                const half8_t a = *reinterpret_cast<const half8_t*>(s_stage + k_addr[t % NKA] + (SOFF + (t / NKA) * 256));
-                s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
+                for (int t = 0; t < NKS; ++t)
+                    a[t] = *reinterpret_cast<const half8_t*>(s_stage + k_addr[t % NKA] + (SOFF + (t / NKA) * 256));
+#pragma unroll
+                for (int t = 0; t < NKS; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t], qreg[t], s, 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+#pragma unroll
+                for (int t = 0; t < NKS - AHEAD; ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, AHEAD, 0);
+            } else {
+#pragma unroll
+                for (int t = 0; t < NKS; ++t) {
+                    const half8_t a = *reinterpret_cast<const half8_t*>(s_stage + k_addr[t % NKA] + (SOFF + (t / NKA) * 256));
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
+                }
             }
             finish_tile(s, base, !alibi && base + kKeyTile - 1 <= wq0, stage_c);
         }
