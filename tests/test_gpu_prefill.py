@@ -128,6 +128,38 @@ def test_benchmark_prompt_shapes_sampled_rows(name, B, N0, Hq, Hkv, D):
     assert np.all(np.isfinite(got.astype(np.float32))), "non-finite output outside the sampled rows"
 
 
+WORK_ORDER_SHAPES = [
+    # B, N0, Hq, Hkv, D: how the (request, head, query block) items fall on the XCDs
+    (5, 700, 6, 3, 128),      # 30 heads: XCD shares of 4 and 3 heads, one group each
+    (2, 1500, 56, 8, 256),    # 14 heads per XCD in three groups of 5, 5 and 4
+    (1, 12837, 2, 1, 128),    # more query blocks per head (101) than work-group slots per XCD
+    (3, 257, 1, 1, 64),       # fewer heads than XCDs: most shares are empty
+    (1, 900, 9, 9, 128),      # 9 heads: one XCD with two, seven with one
+]
+
+
+@pytest.mark.parametrize("B,N0,Hq,Hkv,D", WORK_ORDER_SHAPES)
+def test_every_query_block_of_every_head_is_computed(B, N0, Hq, Hkv, D):
+    # the output starts as NaN: a (request, head, block) item that no work-group took, or
+    # took twice with different operands, shows up in the finite check or in the sampled rows
+    from oracle import segkv_oracle as oracle
+    print(f"\n[case] prefill work order B={B} N0={N0} Hq={Hq} Hkv={Hkv} D={D}", flush=True)
+    q, k, v = _draw(B, N0, Hq, Hkv, D, 4242)
+    scale = 1.0 / np.sqrt(D)
+    got = _run(q, k, v, scale)
+    assert np.all(np.isfinite(got.astype(np.float32))), "rows left unwritten"
+    rng = np.random.default_rng(9)
+    blk = 256 if D == 256 else 128
+    fixed = [(b, t, h) for b in range(B) for h in range(Hq)
+             for t in sorted({0, min(N0 - 1, blk - 1), min(N0 - 1, blk), N0 - 1})]
+    rnd = np.stack([rng.integers(0, B, 200), rng.integers(0, N0, 200), rng.integers(0, Hq, 200)], 1)
+    rows = np.concatenate([np.asarray(fixed, dtype=np.int64), rnd]).astype(np.int32)
+    if len(rows) > 700:
+        rows = rows[rng.permutation(len(rows))[:700]]
+    ref = oracle.sdpa_prefill(q, k, v, scale, rows=rows)
+    assert_parity(got[rows[:, 0], rows[:, 1], rows[:, 2]], ref, f"prefill work order N0={N0} D={D}")
+
+
 def test_prefill_then_first_decode_step_share_the_prompt_segment():
     # K/V given to prefill are handed unchanged to the decode kernel as the
     # prompt segment; the decode step (beam 1, T = 1) at position N0 must match
