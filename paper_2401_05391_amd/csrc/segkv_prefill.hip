@@ -9,15 +9,17 @@
 // orientation as the decode kernel:
 //     S^T[key][query]  = K[key][:]   . Q^T[:][query]
 //     O^T[d][query]   += V^T[d][key] . P^T[key][query]
-// A work-group of 4 waves owns 128 consecutive query tokens of one (request,
-// query head); each wave holds 32 of them as the N dimension (Q^T operand in
-// registers) and walks the key tiles 0 .. its own diagonal.  K/V tiles of 32
-// keys are staged once per work-group into double-buffered LDS (one barrier
-// per tile) and read by all four waves; the V^T operand comes out of LDS with
-// the transposing read.  Later query blocks have more keys to visit, so they
-// are scheduled first.  Two kernels: sdpa_prefill_mfma_kernel<D> stages the
-// tiles through registers (D = 64, 256); sdpa_prefill_direct_kernel (D = 128)
-// copies them from global memory straight into LDS, three tiles deep.
+// A work-group of 4 waves (8 at D = 256) owns 128 (256) consecutive query tokens
+// of one (request, query head); each wave holds 32 of them as the N dimension
+// (Q^T operand in registers) and walks the key tiles 0 .. its own diagonal.  K/V
+// tiles of 32 keys are shared by the group's waves through LDS (one barrier per
+// tile); the V^T operand comes out of LDS with the transposing read.  Two
+// kernels: sdpa_prefill_direct_kernel<D> (D = 128, 256) copies the tiles from
+// global memory straight into LDS, three tiles deep, and stores its output from
+// registers; sdpa_prefill_mfma_kernel<D> stages them through registers into
+// double-buffered LDS (D = 64, a zero scale, and the tests' second
+// implementation).  The order in which the (request, head, query block) items
+// are taken is described at prefill_work_item.
 #include <algorithm>
 #include <cstdlib>
 #include <type_traits>
