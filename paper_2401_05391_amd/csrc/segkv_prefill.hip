@@ -591,6 +591,9 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         if (ti + 2 < n_tiles) issue(ti + 2, (STAGE + 2) % NSTAGE);
         const int base = ti * kKeyTile;
         if (base <= wq0 + kQueryTile - 1) {
+            // (the wave that is about to issue the dependent Q.K^T chain goes first on its SIMD:
+            // +0.2-1 %; the same around the P.V product measured 3 % slower)
+            __builtin_amdgcn_s_setprio(2);
             float16_t s;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.0f;
@@ -619,6 +622,7 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
                     s = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[t], s, 0, 0, 0);
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
             finish_tile(s, base, !alibi && base + kKeyTile - 1 <= wq0, stage_c);
         }
     };
