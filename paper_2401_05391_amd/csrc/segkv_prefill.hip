@@ -431,8 +431,10 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
             }
         }
     };
+    // all three stages are free at the start: the first three tiles go out together, ahead of Q
     issue(0, 0);
     if (n_tiles > 1) issue(1, 1);
+    if (n_tiles > 2) issue(2, 2);
 
     // ---- Q^T operand in registers ----
     half8_t qreg[NKS];
@@ -588,7 +590,7 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
         if (ti + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * INS_PER_WAVE));
         else                  __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();      // everybody's have; and everybody is done with tile ti-1's stage
-        if (ti + 2 < n_tiles) issue(ti + 2, (STAGE + 2) % NSTAGE);
+        if (ti > 0 && ti + 2 < n_tiles) issue(ti + 2, (STAGE + 2) % NSTAGE);   // (tile 2 went out with 0 and 1)
         const int base = ti * kKeyTile;
         if (base <= wq0 + kQueryTile - 1) {
             // (the wave that is about to issue the dependent Q.K^T chain goes first on its SIMD:
