@@ -160,6 +160,33 @@ def test_every_query_block_of_every_head_is_computed(B, N0, Hq, Hkv, D):
     assert_parity(got[rows[:, 0], rows[:, 1], rows[:, 2]], ref, f"prefill work order N0={N0} D={D}")
 
 
+def _random_prefill_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        D = int(rng.choice([64, 128, 128, 256]))
+        Hkv = int(rng.choice([1, 2, 3, 5, 8]))
+        G = int(rng.choice([1, 1, 2, 4]))
+        B = int(rng.integers(1, 5))
+        N0 = int(rng.choice([rng.integers(1, 40), rng.integers(40, 300), rng.integers(300, 900)]))
+        shapes.append((B, N0, Hkv * G, Hkv, D, bool(rng.integers(0, 2)), float(rng.choice([1.0, -1.0]))))
+    return shapes
+
+
+@pytest.mark.parametrize("B,N0,Hq,Hkv,D,alibi,sign", _random_prefill_shapes(16, 20240))
+def test_prefill_random_shapes(B, N0, Hq, Hkv, D, alibi, sign):
+    # seeded random dimensions: ragged lengths around the tile and block sizes, grouped heads,
+    # head counts that do not divide among the XCDs, both signs of the scale
+    from oracle import segkv_oracle as oracle
+    print(f"\n[case] prefill random B={B} N0={N0} Hq={Hq} Hkv={Hkv} D={D} alibi={alibi} sign={sign}", flush=True)
+    q, k, v = _draw(B, N0, Hq, Hkv, D, 31 * N0 + Hq)
+    slopes = alibi_slopes(Hq) if alibi else None
+    scale = sign / np.sqrt(D)
+    ref = oracle.sdpa_prefill(q, k, v, scale, slopes=slopes)
+    got = _run(q, k, v, scale, slopes)
+    assert_parity(got, ref, f"prefill random N0={N0} D={D}")
+
+
 def test_prefill_then_first_decode_step_share_the_prompt_segment():
     # K/V given to prefill are handed unchanged to the decode kernel as the
     # prompt segment; the decode step (beam 1, T = 1) at position N0 must match
