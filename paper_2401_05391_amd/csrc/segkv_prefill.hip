@@ -535,14 +535,40 @@ void sdpa_prefill_direct_kernel(PrefillParams p)
             pb[r >> 3][r & 7] = pp.x;
             pb[r >> 3][(r & 7) + 1] = pp.y;
         }
+        if constexpr (D == 256) {
+            // as for the K operands: the V^T operands (two transposing reads each) run
+            // V_AHEAD products ahead of their MFMAs
+            constexpr int V_AHEAD = 4;
+            half4_t va[2 * NDB][2];
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
+            for (int i = 0; i < 2 * NDB; ++i) {
+                const int db = i >> 1, u = i & 1;
+                va[i][0] = lds_read_tr16(s_stage + v_addr[db % NVA] + (SOFF + (db / NVA) * 256 + (16 * u) * ROWB));
+                va[i][1] = lds_read_tr16(s_stage + v_addr[db % NVA] + (SOFF + (db / NVA) * 256 + (16 * u + 8) * ROWB));
+            }
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const half4_t lo = lds_read_tr16(s_stage + v_addr[db % NVA] + (SOFF + (db / NVA) * 256 + (16 * u) * ROWB));
-                const half4_t hi = lds_read_tr16(s_stage + v_addr[db % NVA] + (SOFF + (db / NVA) * 256 + (16 * u + 8) * ROWB));
+            for (int i = 0; i < 2 * NDB; ++i) {
+                const half4_t lo = va[i][0], hi = va[i][1];
                 const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
+                o_acc[i >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[i & 1], o_acc[i >> 1], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * V_AHEAD, 0);
+#pragma unroll
+            for (int i = 0; i < 2 * NDB - V_AHEAD; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, V_AHEAD, 0);
+        } else {
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const half4_t lo = lds_read_tr16(s_stage + v_addr[db % NVA] + (SOFF + (db / NVA) * 256 + (16 * u) * ROWB));
+                    const half4_t hi = lds_read_tr16(s_stage + v_addr[db % NVA] + (SOFF + (db / NVA) * 256 + (16 * u + 8) * ROWB));
+                    const half8_t a = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[u], o_acc[db], 0, 0, 0);
+                }
             }
         }
     };
