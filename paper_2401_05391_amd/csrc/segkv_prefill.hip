@@ -43,7 +43,7 @@ constexpr int prefill_waves(int D) { return D <= 128 ? 4 : 8; }
 // finishes.  Both are met as follows.  The heads are split evenly among the 8 XCDs (the
 // hardware sends work-group i to XCD i mod 8; the grid is padded to 8 equal shares and the
 // surplus work-groups leave at once).  Each XCD takes its heads in groups of about as many
-// as fill its work-group slots once (heads_per_group x blocks per head), and deals each
+// as fill its work-group slots twice (heads_per_group x blocks per head), and deals each
 // group's blocks longest first ACROSS the group's heads: what runs together still belongs
 // to those few heads, and every group -- the XCD's last one too -- ends with its shortest
 // blocks.  Heads that share a KV head (grouped queries) are neighbours within a group.
@@ -675,10 +675,13 @@ hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
     const unsigned grid = (unsigned)prefill_grid_size(p.B * p.Hq, n_qblocks);
     const dim3 block(nw * 64);
     // work-group slots of one XCD (32 CUs; work-groups per CU as the kernels' registers and
-    // LDS allow: 4 / 3 / 1 at D = 64 / 128 / 256) filled once by a group of heads
+    // LDS allow: 4 / 3 / 1 at D = 64 / 128 / 256), the measure of a group of heads
     PrefillParams q = p;
     const int slots_per_xcd = 32 * (D == 64 ? 4 : D == 128 ? 3 : 1);
-    q.heads_per_group = std::max(1, slots_per_xcd / n_qblocks);
+    // Two rounds of slots per group measured best on the multi-head shapes (one: -1 %, four: -4
+    // to -8 %, the K/V of too many heads then compete for the L2); query heads that share a KV head
+    // cost the L2 nothing extra, so grouped-query shapes take G times as many (70B-2k: +4 %).
+    q.heads_per_group = std::max(1, 2 * slots_per_xcd / n_qblocks) * std::max(1, p.G);
     switch (D) {
         case 64:  return SEGKV_LAUNCH(sdpa_prefill_mfma_kernel<64>, dim3(grid), block, st, q);
         case 128:
