@@ -420,8 +420,18 @@ def mfma_sustained_rates(segkv, torch):
     return res
 
 
+def relate_to_sustained_rate(rows, rates):
+    """Each prefill shape's TFLOP/s as a fraction of what the matrix cores sustained on random
+    register operands in the same process (the power limit differs from one box to the next)."""
+    ref = rates["random_operands"]["tflops"]
+    for r in rows:
+        r["frac_of_mfma_sustained_random_operands"] = r["tflops"] / ref
+
+
 def prefill_bench(steps, warmup, segkv, torch):
     rows = prefill_rows(steps, warmup, segkv, torch)
+    rates = mfma_sustained_rates(segkv, torch)
+    relate_to_sustained_rate(rows, rates)
     head = rows[0]
     return {"metric": "prefill causal SDPA (segkv_sdpa_prefill): achieved fp16 TFLOP/s",
             "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -429,7 +439,7 @@ def prefill_bench(steps, warmup, segkv, torch):
             "vs_baseline": None, "dtype": "f16", "data": "synthetic",
             "config": {"workload": head["workload"], **head["shape"]},
             "roofline": head["roofline"], "cpu_baseline": None, "shapes": rows,
-            "mfma_sustained": mfma_sustained_rates(segkv, torch)}
+            "mfma_sustained": rates}
 
 
 def fig6_rows(steps, warmup, segkv, torch):
@@ -625,6 +635,8 @@ def main():
     fig6 = None if a.no_extras else fig6_rows(a.steps, a.warmup, segkv, torch)
     prefill = None if a.no_extras else prefill_rows(max(a.steps // 4, 10), a.warmup, segkv, torch)
     mfma_rates = None if a.no_extras else mfma_sustained_rates(segkv, torch)
+    if prefill is not None:
+        relate_to_sustained_rate(prefill, mfma_rates)
 
     calibration = None
     if a.calibrate_counters:
