@@ -30,6 +30,11 @@
 
 namespace segkv {
 
+// The kernels keep the logits in the units of the raw products and divide the bias by the
+// scale.  Below this |scale * log2 e| the product's share of a logit is far under fp32
+// resolution next to any bias, the division would overflow, and the scale counts as zero.
+constexpr float kTinyScale2 = 1.0e-30f;
+
 // Waves per work-group (each holds 32 query tokens).  D <= 128: four, two
 // work-groups per CU, so that one group's barrier waits overlap the other's
 // work.  D = 256: eight -- the accumulators leave room for two waves per SIMD
@@ -130,7 +135,7 @@ void sdpa_prefill_mfma_kernel(PrefillParams p)
     // applied inside the exponent's multiply-add.  A zero scale leaves only the bias: then
     // every tile takes the masked path, which drops the product (raw_w = 0) and keeps the
     // bias in final units (mult = 1).
-    const bool zero_scale = scale2 == 0.0f;
+    const bool zero_scale = scale2 < kTinyScale2;
     const float raw_w = zero_scale ? 0.0f : 1.0f;
     const float bias_raw = zero_scale ? slope2 : slope2 / scale2;
     const float mult = zero_scale ? 1.0f : scale2;
@@ -669,7 +674,7 @@ hipError_t launch_sdpa_prefill(const PrefillParams& p, int D, hipStream_t st)
     // tiles copied straight into LDS at D = 128 and 256 (a zero scale goes the other way: the
     // direct kernels divide the bias by the scale); the test-only override keeps the
     // register-staged kernels
-    const bool direct = (D == 128 || D == 256) && !tuning().prefill_regs && p.scale2 != 0.0f;
+    const bool direct = (D == 128 || D == 256) && !tuning().prefill_regs && fabsf(p.scale2) >= kTinyScale2;
     const int nw = direct ? direct_waves(D) : prefill_waves(D);
     const int n_qblocks = (p.N0 + nw * kQueryTile - 1) / (nw * kQueryTile);
     const unsigned grid = (unsigned)prefill_grid_size(p.B * p.Hq, n_qblocks);

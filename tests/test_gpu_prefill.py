@@ -61,7 +61,7 @@ def test_prefill_matches_oracle(B, N0, Hq, Hkv, D, alibi, staging, planner_env):
 
 
 @pytest.mark.parametrize("staging", ["direct", "regs"])
-@pytest.mark.parametrize("D,scale,alibi", [(128, -0.11, False), (128, 0.0, True), (128, 0.0, False),
+@pytest.mark.parametrize("D,scale,alibi", [(128, -0.11, False), (128, 0.0, True), (128, 0.0, False), (128, 1e-36, True),
                                            (64, -0.2, True), (256, -0.07, False), (64, 0.0, True)])
 def test_prefill_negative_and_zero_scale(D, scale, alibi, staging, planner_env):
     # the kernels keep the logits in the units of the raw products and move the sign of
